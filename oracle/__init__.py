@@ -1,0 +1,207 @@
+"""ctypes front end of the CPU oracle (oracle/diloco_oracle.cpp).  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg import this
+package.  It imports nothing from the GPU package, and the GPU package never imports it.
+All arrays are C-contiguous numpy arrays that the C++ side updates in place.
+"""
+import ctypes as C
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(_build.build())
+        sz, f32, f64, u16, i32, u32, u64, vp = (C.c_size_t, C.c_float, C.c_double, C.c_uint16,
+                                                C.c_int32, C.c_uint32, C.c_uint64, C.c_void_p)
+        sig = {
+            "oracle_f32_to_f16_rne": (u16, [f32]),
+            "oracle_f16_to_f32": (f32, [u16]),
+            "oracle_cast_f32_to_f16": (None, [vp, vp, sz]),
+            "oracle_cast_pattern_range": (None, [u32, sz, vp]),
+            "oracle_cast_f16_to_f32": (None, [vp, vp, sz]),
+            "oracle_adamw_step_f32": (None, [vp, vp, vp, vp, sz, f64, f64, f64, f64, f64, vp, vp]),
+            "oracle_adamw_step_f64": (None, [vp, vp, vp, vp, sz, f64, f64, f64, f64, f64, vp, vp]),
+            "oracle_unscale_f16": (None, [vp, f32, vp, sz]),
+            "oracle_found_inf_f16": (i32, [vp, sz]),
+            "oracle_found_inf_f32": (i32, [vp, sz]),
+            "oracle_pseudo_grad_f32": (None, [vp, vp, vp, sz]),
+            "oracle_pseudo_grad_f64": (None, [vp, vp, vp, sz]),
+            "oracle_round_through_f16": (None, [vp, sz]),
+            "oracle_replica_mean_f32": (None, [vp, sz, sz, vp]),
+            "oracle_replica_mean_f64": (None, [vp, sz, sz, vp]),
+            "oracle_nesterov_step_f32": (None, [vp, vp, vp, sz, f64, f64]),
+            "oracle_nesterov_step_f64": (None, [vp, vp, vp, sz, f64, f64]),
+            "oracle_outer_step_f32": (None, [vp, vp, vp, sz, sz, f64, f64, i32, vp, vp]),
+            "oracle_plan_layout": (u64, [vp, u32, u64, u64, vp]),
+            "oracle_num_threads": (C.c_int, []),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def _p(a, dtype):
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags["C_CONTIGUOUS"], \
+        (type(a), getattr(a, "dtype", None), dtype)
+    return a.ctypes.data
+
+
+# ---- binary16 casts ---------------------------------------------------------
+def f32_to_f16_bits(x):
+    """RNE cast of a float32 array to binary16 bit patterns (uint16)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    lib().oracle_cast_f32_to_f16(_p(x, np.float32), _p(out, np.uint16), x.size)
+    return out
+
+
+def cast_pattern_range(first, n):
+    """binary16 codes of the n consecutive float32 bit patterns starting at `first`."""
+    out = np.empty(n, dtype=np.uint16)
+    lib().oracle_cast_pattern_range(int(first) & 0xFFFFFFFF, n, _p(out, np.uint16))
+    return out
+
+
+def f16_bits_to_f32(h):
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    out = np.empty(h.shape, dtype=np.float32)
+    lib().oracle_cast_f16_to_f32(_p(h, np.uint16), _p(out, np.float32), h.size)
+    return out
+
+
+# ---- inner step -------------------------------------------------------------
+class AdamWState:
+    """One worker's AdamW state: weights, moments, running products beta^t, step count."""
+
+    def __init__(self, theta, dtype=np.float32):
+        self.dtype = np.dtype(dtype)
+        self.theta = np.array(theta, dtype=self.dtype, order="C").reshape(-1)
+        self.m = np.zeros_like(self.theta)
+        self.v = np.zeros_like(self.theta)
+        self.p1 = C.c_double(1.0)
+        self.p2 = C.c_double(1.0)
+        self.t = 0
+
+
+def adamw_step(st, g, lr, beta1, beta2, eps, weight_decay):
+    """One AdamW step of one worker, in place on st (float32 or float64 state)."""
+    g = np.ascontiguousarray(g, dtype=st.dtype).reshape(-1)
+    assert g.size == st.theta.size
+    fn = lib().oracle_adamw_step_f32 if st.dtype == np.float32 else lib().oracle_adamw_step_f64
+    fn(_p(st.theta, st.dtype), _p(st.m, st.dtype), _p(st.v, st.dtype), _p(g, st.dtype),
+       st.theta.size, lr, beta1, beta2, eps, weight_decay, C.addressof(st.p1), C.addressof(st.p2))
+    st.t += 1
+
+
+def unscale_f16(g16_bits, inv_scale):
+    """widen(binary16 gradient) * inv_scale, as float32."""
+    g16_bits = np.ascontiguousarray(g16_bits, dtype=np.uint16).reshape(-1)
+    out = np.empty(g16_bits.size, dtype=np.float32)
+    lib().oracle_unscale_f16(_p(g16_bits, np.uint16), inv_scale, _p(out, np.float32), out.size)
+    return out
+
+
+def found_inf(g):
+    """1 if any element of g (float32 array, or uint16 array of binary16 codes) is inf/NaN."""
+    g = np.ascontiguousarray(g).reshape(-1)
+    if g.dtype == np.uint16:
+        return int(lib().oracle_found_inf_f16(_p(g, np.uint16), g.size))
+    return int(lib().oracle_found_inf_f32(_p(g, np.float32), g.size))
+
+
+# ---- outer step -------------------------------------------------------------
+def pseudo_grad(theta0, theta_r):
+    dt = theta0.dtype
+    out = np.empty_like(theta0)
+    fn = lib().oracle_pseudo_grad_f32 if dt == np.float32 else lib().oracle_pseudo_grad_f64
+    fn(_p(theta0, dt), _p(theta_r, dt), _p(out, dt), theta0.size)
+    return out
+
+
+def round_through_f16(delta):
+    lib().oracle_round_through_f16(_p(delta, np.float32), delta.size)
+    return delta
+
+
+def replica_mean(delta):
+    """delta: [k][n] -> mean over k (sequential sum, then divide by k)."""
+    k, n = delta.shape
+    dt = delta.dtype
+    out = np.empty(n, dtype=dt)
+    fn = lib().oracle_replica_mean_f32 if dt == np.float32 else lib().oracle_replica_mean_f64
+    fn(_p(delta, dt), k, n, _p(out, dt))
+    return out
+
+
+def nesterov_step(theta0, b, grad, lr, mu):
+    dt = theta0.dtype
+    fn = lib().oracle_nesterov_step_f32 if dt == np.float32 else lib().oracle_nesterov_step_f64
+    fn(_p(theta0, dt), _p(b, dt), _p(grad, dt), theta0.size, lr, mu)
+
+
+def outer_step(theta0, b, theta, outer_lr, mu, pg_f16):
+    """Whole outer step, float32, in place.  theta is [k][n]."""
+    k, n = theta.shape
+    d = np.empty((k, n), dtype=np.float32)
+    mean = np.empty(n, dtype=np.float32)
+    lib().oracle_outer_step_f32(_p(theta0, np.float32), _p(b, np.float32), _p(theta, np.float32),
+                                k, n, outer_lr, mu, 1 if pg_f16 else 0, _p(d, np.float32),
+                                _p(mean, np.float32))
+    return mean
+
+
+# ---- layout -------------------------------------------------------------------
+def plan_layout(numel, align, tile):
+    numel = np.ascontiguousarray(numel, dtype=np.uint64)
+    off = np.empty(numel.size, dtype=np.uint64)
+    n_pad = lib().oracle_plan_layout(_p(numel, np.uint64), numel.size, align, tile,
+                                     _p(off, np.uint64))
+    return off, int(n_pad)
+
+
+def num_threads():
+    return int(lib().oracle_num_threads())
+
+
+# ---- the whole method over k workers (plain driver around the steps above) ----
+class DiLoCoOracle:
+    """k workers, each with its own AdamW state, plus the outer weights theta0 and the
+    outer momentum buffer b.  float32 throughout.  A worker whose found_inf flag is set
+    skips its inner step entirely (weights, moments and step count stay as they are)."""
+
+    def __init__(self, theta_init, k, inner_lr, beta1, beta2, eps, weight_decay, outer_lr,
+                 outer_momentum, pg_f16=False):
+        theta_init = np.ascontiguousarray(theta_init, dtype=np.float32).reshape(-1)
+        self.k = k
+        self.hp = (inner_lr, beta1, beta2, eps, weight_decay)
+        self.outer_lr, self.mu, self.pg_f16 = outer_lr, outer_momentum, pg_f16
+        self.theta0 = theta_init.copy()
+        self.b = np.zeros_like(self.theta0)
+        self.workers = [AdamWState(theta_init) for _ in range(k)]
+
+    def inner_step(self, grads, found_inf_flags=None, lr=None, inv_scale=None):
+        """grads[r]: float32 array, or uint16 binary16 codes together with inv_scale."""
+        lr0, b1, b2, eps, wd = self.hp
+        for r, st in enumerate(self.workers):
+            if found_inf_flags is not None and found_inf_flags[r]:
+                continue
+            g = grads[r]
+            if g.dtype == np.uint16:
+                g = unscale_f16(g, inv_scale)
+            adamw_step(st, g, lr0 if lr is None else lr, b1, b2, eps, wd)
+
+    def outer_step(self):
+        theta = np.stack([st.theta for st in self.workers])
+        mean = outer_step(self.theta0, self.b, theta, self.outer_lr, self.mu, self.pg_f16)
+        for r, st in enumerate(self.workers):
+            st.theta[:] = theta[r]
+        return mean
