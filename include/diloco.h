@@ -1,0 +1,165 @@
+/* diloco.h -- C ABI of the MI355X (gfx950) DiLoCo optimizer hot path.
+ *
+ * The method (OpenDiLoCo, arxiv 2407.07852, Section "Implementation" and Figure 1): k workers
+ * each hold a replica of the model and run an inner optimizer (AdamW) for H local steps; then
+ * an outer optimizer (SGD with Nesterov momentum) is applied to the weights theta(t) all
+ * workers started the round from, using as its gradient the average over workers of the
+ * pseudo-gradients  delta_r = theta(t) - theta_r(t+H).  Every worker then restarts from the
+ * new outer weights.  Pseudo-gradients are FP32, optionally FP16 (Section "All-Reduce in
+ * FP16").  With FP16 mixed precision a gradient scaler acts in the inner step only
+ * (Section "Implementation", paragraph "General Implementation Details").
+ *
+ * Here all k replicas live on ONE GPU in a single caller-owned arena of flat, padded
+ * multi-tensor buffers, and each step is one fused streaming kernel:
+ *
+ *   arena (FP32):  theta0[n_pad]  mom[n_pad]  theta[k][stride]  m[k][stride]  v[k][stride]
+ *
+ * theta0 = outer weights theta(t); mom = outer momentum buffer; theta/m/v = each worker's
+ * weights and AdamW moments.  Every tensor of the parameter list starts at a multiple of 64
+ * elements inside each buffer; the gaps and the tail up to n_pad hold zeros and stay zero.
+ *
+ * Conventions
+ *   - "device" pointers are GPU global memory; "host" pointers are ordinary process memory.
+ *   - The caller owns every large allocation (arena, gradients, flags).  The library borrows
+ *     them; it allocates only O(k) bytes of device state of its own.
+ *   - Every call returns DILOCO_OK (0), a positive informational code, or a negative error.
+ *     On an error nothing has been launched.  No exception or abort crosses this boundary.
+ *   - All device work is enqueued asynchronously on the stream given at init.
+ *   - One context may be used by one host thread at a time.
+ *   - The library fails loudly (DILOCO_ERR_HIP) when no usable GPU runtime is present; there
+ *     is no CPU fallback.
+ */
+#ifndef DILOCO_H
+#define DILOCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct diloco_ctx diloco_ctx; /* opaque, host side */
+
+enum {
+  DILOCO_OK = 0,
+  DILOCO_ROUND_COMPLETE = 1,       /* informational: the H-th inner step since the last outer step */
+  DILOCO_ERR_INVALID_ARG = -1,     /* NULL, zero sizes, unknown dtype, hyper-parameter out of range */
+  DILOCO_ERR_ALIGN = -2,           /* a device pointer or stride is not aligned for 128-bit access */
+  DILOCO_ERR_ARENA_TOO_SMALL = -3, /* arena_bytes below what diloco_query_layout reports */
+  DILOCO_ERR_HIP = -4,             /* the HIP runtime reported an error (also: asynchronous faults) */
+  DILOCO_ERR_STATE = -5            /* call sequence error (e.g. flags passed without a check) */
+};
+
+enum { DILOCO_F32 = 0, DILOCO_F16 = 1 }; /* element type of pseudo-gradients / gradients */
+
+enum { /* diloco_get_buffer selector */
+  DILOCO_BUF_THETA0 = 0, /* outer weights theta(t), [n_pad] */
+  DILOCO_BUF_MOM = 1,    /* outer Nesterov momentum buffer, [n_pad] */
+  DILOCO_BUF_THETA = 2,  /* worker weights, replica r at + r*stride */
+  DILOCO_BUF_M = 3,      /* AdamW first moment */
+  DILOCO_BUF_V = 4       /* AdamW second moment */
+};
+
+#define DILOCO_MAX_WORKERS 64
+#define DILOCO_TENSOR_ALIGN 64u /* elements: every tensor starts on a 256-byte boundary */
+#define DILOCO_TILE 8192u       /* elements: n_pad is a multiple of this */
+
+/* Problem statement: the parameter tensor list, the two optimizers' hyper-parameters
+ * (Appendix A, Table 3 gives inner lr 4e-4, weight decay 0.1, outer lr 0.7, outer momentum
+ * 0.9; betas and eps are not printed by the paper), H, k and the pseudo-gradient type. */
+typedef struct {
+  uint32_t n_tensors;       /* >= 1 */
+  const uint64_t* numel;    /* host array [n_tensors], each >= 1; copied at init */
+  uint32_t k_workers;       /* 1 .. DILOCO_MAX_WORKERS */
+  uint32_t h_inner_steps;   /* H; only used to report DILOCO_ROUND_COMPLETE; 0 = never */
+  double inner_lr;          /* AdamW: >= 0, finite */
+  double beta1, beta2;      /* in [0, 1) */
+  double eps;               /* > 0 */
+  double weight_decay;      /* >= 0 (decoupled) */
+  double outer_lr;          /* Nesterov SGD: >= 0, finite */
+  double outer_momentum;    /* in [0, 1) */
+  int32_t pg_dtype;         /* DILOCO_F32, or DILOCO_F16: round each worker's pseudo-gradient to
+                               IEEE binary16 (nearest-even, subnormals kept, overflow to inf) and
+                               widen it back before the FP32 average */
+  void* arena;              /* device, caller-owned, 256-byte aligned; unused by query_layout */
+  uint64_t arena_bytes;
+  void* stream;             /* hipStream_t, borrowed; NULL = the default stream */
+} diloco_config;
+
+typedef struct {
+  uint64_t n_pad;       /* padded elements per flat buffer (multiple of DILOCO_TILE) */
+  uint64_t stride;      /* elements between consecutive replicas of theta / m / v */
+  uint64_t arena_bytes; /* bytes the arena must provide */
+  uint64_t off_theta0, off_mom, off_theta, off_m, off_v; /* byte offsets inside the arena */
+} diloco_layout;
+
+/* Flat layout for cfg's tensor list and k (host only, touches no GPU).  tensor_offsets may be
+ * NULL; otherwise it receives n_tensors element offsets, valid inside every flat buffer (and
+ * inside the caller's gradient buffers). */
+int diloco_query_layout(const diloco_config* cfg, diloco_layout* out, uint64_t* tensor_offsets);
+
+/* Creates a context over cfg->arena.  init_params: host array of n_tensors DEVICE pointers to
+ * FP32 tensors that are packed into theta0; or NULL when theta0 in the arena already holds the
+ * flat padded weights.  Then (Figure 1's starting state) every worker's weights are set to
+ * theta0, moments and the outer momentum buffer to zero, step counts to zero; pads are zeroed.
+ * *out is set only on success. */
+int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco_ctx** out);
+
+/* Gradient-scaler support for the inner step (mixed precision; Section "Implementation").
+ * grads: device, [k][grad_stride] elements of grad_dtype, laid out like the flat buffers
+ * (pads must be zero or at least finite).  Sets found_inf[r] (device, k int32) to 1 if any
+ * element of worker r's gradient is +-inf or NaN, else 0, and records inv_scale (finite, > 0)
+ * as the factor the next diloco_inner_step applies to these gradients.  The gradients are
+ * not modified: the multiply is fused into the inner step. */
+int diloco_unscale_check(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
+                         int32_t grad_dtype, float inv_scale, int32_t* found_inf);
+
+/* One AdamW step of all k workers in one launch:
+ *   g = grad (* inv_scale when found_inf is given)
+ *   m = beta1*m + (1-beta1)*g ;  v = beta2*v + (1-beta2)*g*g
+ *   theta = theta - lr*wd*theta - lr * (m/(1-beta1^t)) / (sqrt(v/(1-beta2^t)) + eps)
+ * with t the worker's own step count.  grads as in diloco_unscale_check (grad_stride >= n_pad,
+ * a multiple of 8 elements; base 16-byte aligned).  lr < 0 selects cfg->inner_lr.
+ * found_inf: NULL, or the device flags written by the preceding diloco_unscale_check (else
+ * DILOCO_ERR_STATE); a worker whose flag is set skips the step: its weights, moments and step
+ * count stay untouched.  Returns DILOCO_ROUND_COMPLETE on every H-th call since the last outer
+ * step. */
+int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
+                      int32_t grad_dtype, double lr, const int32_t* found_inf);
+
+/* The outer step of Figure 1, fused into one launch:
+ *   delta_r = theta0 - theta_r            (optionally rounded through binary16)
+ *   dbar    = (delta_0 + ... + delta_{k-1}) / k        (FP32, workers in ascending order)
+ *   mom     = mu*mom + dbar ;  theta0 = theta0 - outer_lr*(dbar + mu*mom)
+ *   theta_r = theta0 for every r.
+ * AdamW moments and step counts are not touched.  Legal after any number of inner steps,
+ * including none.  The gradient scaler plays no part here. */
+int diloco_outer_step(diloco_ctx* ctx);
+
+/* Device address of a flat buffer (replica ignored for THETA0 / MOM). */
+int diloco_get_buffer(diloco_ctx* ctx, int which, uint32_t replica, void** dev_ptr);
+
+int diloco_get_layout(diloco_ctx* ctx, diloco_layout* out);
+
+/* Per-worker AdamW step counts t_r into the host array steps[k].  Synchronises the stream. */
+int diloco_get_steps(diloco_ctx* ctx, uint32_t* steps);
+
+/* The pseudo-gradient's FP32 -> binary16 rounding on its own, as the outer step applies it
+ * (Section "All-Reduce in FP16"): in/out are device arrays of n elements (out: uint16 codes). */
+int diloco_cast_f32_to_f16(const float* in, uint16_t* out, uint64_t n, void* stream);
+
+/* Launch-shape knobs for benchmarking sweeps; results never depend on them.  Unknown names
+ * return DILOCO_ERR_INVALID_ARG. */
+int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value);
+
+/* Message of the most recent error on this context (ctx may be NULL: the calling thread's
+ * last error from diloco_init / diloco_query_layout).  Never NULL. */
+const char* diloco_last_error(diloco_ctx* ctx);
+
+int diloco_destroy(diloco_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,433 @@
+// C ABI of the DiLoCo optimizer hot path (see include/diloco.h): argument validation, the
+// flat layout planner, the context, and the kernel launches.  Host code only.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/diloco.h"
+#include "internal.h"
+
+using namespace diloco;
+
+struct diloco_ctx {
+  diloco_config cfg;               // numel pointer re-targeted to `numel` below
+  std::vector<uint64_t> numel;
+  std::vector<uint64_t> offsets;
+  diloco_layout lay;
+  hipStream_t stream;
+  int device;
+  int n_cu;
+  RepState* d_state;               // device, [2][k]
+  int parity;                      // which half of d_state is current
+  uint32_t steps_since_outer;
+  bool have_scale;                 // an unscale_check has recorded (flags, inv_scale)
+  float inv_scale;
+  const int32_t* checked_flags;
+  const void* checked_grads;
+  Tuning tune;
+  std::string err;
+};
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(diloco_ctx* ctx, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf;
+  g_err = buf;
+  return code;
+}
+
+int fail_hip(diloco_ctx* ctx, const char* what, hipError_t e) {
+  return fail(ctx, DILOCO_ERR_HIP, "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+}
+
+uint64_t round_up(uint64_t x, uint64_t to) { return (x + to - 1) / to * to; }
+
+bool finite_in(double x, double lo, bool lo_open, double hi, bool hi_open) {
+  if (!std::isfinite(x)) return false;
+  if (lo_open ? !(x > lo) : !(x >= lo)) return false;
+  if (hi_open ? !(x < hi) : !(x <= hi)) return false;
+  return true;
+}
+
+// Shape / hyper-parameter validation shared by query_layout and init (no GPU involved).
+int validate_problem(const diloco_config* cfg) {
+  if (!cfg) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "config is NULL");
+  if (cfg->n_tensors == 0 || !cfg->numel)
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "empty parameter tensor list");
+  if (cfg->k_workers == 0 || cfg->k_workers > DILOCO_MAX_WORKERS)
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "k_workers must be in 1..%d, got %u",
+                DILOCO_MAX_WORKERS, cfg->k_workers);
+  uint64_t total = 0;
+  for (uint32_t t = 0; t < cfg->n_tensors; ++t) {
+    if (cfg->numel[t] == 0)
+      return fail(nullptr, DILOCO_ERR_INVALID_ARG, "tensor %u has zero elements", t);
+    if (cfg->numel[t] > (1ull << 40) || (total += cfg->numel[t]) > (1ull << 40))
+      return fail(nullptr, DILOCO_ERR_INVALID_ARG, "parameter count exceeds 2^40");
+  }
+  return DILOCO_OK;
+}
+
+int validate_hyper(const diloco_config* cfg) {
+  const double inf = HUGE_VAL;
+  if (!finite_in(cfg->inner_lr, 0, false, inf, true) ||
+      !finite_in(cfg->outer_lr, 0, false, inf, true))
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "learning rates must be finite and >= 0");
+  if (!finite_in(cfg->beta1, 0, false, 1, true) || !finite_in(cfg->beta2, 0, false, 1, true))
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "betas must be in [0, 1)");
+  if (!finite_in(cfg->eps, 0, true, inf, true))
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "eps must be finite and > 0");
+  if (!finite_in(cfg->weight_decay, 0, false, inf, true))
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "weight_decay must be finite and >= 0");
+  if (!finite_in(cfg->outer_momentum, 0, false, 1, true))
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "outer_momentum must be in [0, 1)");
+  if (cfg->pg_dtype != DILOCO_F32 && cfg->pg_dtype != DILOCO_F16)
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "unknown pg_dtype %d", cfg->pg_dtype);
+  return DILOCO_OK;
+}
+
+void plan(const diloco_config* cfg, diloco_layout* lay, uint64_t* offsets) {
+  uint64_t cursor = 0;
+  for (uint32_t t = 0; t < cfg->n_tensors; ++t) {
+    cursor = round_up(cursor, DILOCO_TENSOR_ALIGN);
+    if (offsets) offsets[t] = cursor;
+    cursor += cfg->numel[t];
+  }
+  const uint64_t n_pad = round_up(cursor, DILOCO_TILE);
+  const uint64_t k = cfg->k_workers;
+  lay->n_pad = n_pad;
+  lay->stride = n_pad;
+  lay->off_theta0 = 0;
+  lay->off_mom = n_pad * 4;
+  lay->off_theta = 2 * n_pad * 4;
+  lay->off_m = lay->off_theta + k * lay->stride * 4;
+  lay->off_v = lay->off_m + k * lay->stride * 4;
+  lay->arena_bytes = lay->off_v + k * lay->stride * 4;
+}
+
+// The [ptr, ptr+bytes) range must lie inside one device allocation of the current device.
+int check_device_range(diloco_ctx* ctx, const void* ptr, uint64_t bytes, const char* name) {
+  hipPointerAttribute_t attr;
+  hipError_t e = hipPointerGetAttributes(&attr, ptr);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "%s is not a device pointer (%s)", name,
+                hipGetErrorString(e));
+  }
+  if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "%s is not device memory", name);
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  e = hipMemGetAddressRange(&base, &size, const_cast<void*>(ptr));
+  if (e != hipSuccess) {
+    // Memory the runtime cannot attribute to one allocation (e.g. virtual-memory mappings):
+    // the pointer class was verified above, the extent cannot be.
+    (void)hipGetLastError();
+    return DILOCO_OK;
+  }
+  const uintptr_t lo = (uintptr_t)base, p = (uintptr_t)ptr;
+  if (p < lo || p + bytes > lo + size)
+    return fail(ctx, DILOCO_ERR_INVALID_ARG,
+                "%s: %llu bytes do not fit its allocation (%zu bytes from its base)", name,
+                (unsigned long long)bytes, size - (p - lo));
+  return DILOCO_OK;
+}
+
+float* buf(const diloco_ctx* c, uint64_t off) {
+  return reinterpret_cast<float*>(static_cast<char*>(c->cfg.arena) + off);
+}
+
+int check_grads(diloco_ctx* ctx, const void* grads, uint64_t grad_stride, int32_t grad_dtype) {
+  if (!grads) return fail(ctx, DILOCO_ERR_INVALID_ARG, "grads is NULL");
+  if (grad_dtype != DILOCO_F32 && grad_dtype != DILOCO_F16)
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "unknown grad_dtype %d", grad_dtype);
+  if (grad_stride < ctx->lay.n_pad)
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "grad_stride %llu is below n_pad %llu",
+                (unsigned long long)grad_stride, (unsigned long long)ctx->lay.n_pad);
+  if (((uintptr_t)grads & 15u) != 0 || (grad_stride & 7u) != 0)
+    return fail(ctx, DILOCO_ERR_ALIGN,
+                "grads must be 16-byte aligned and grad_stride a multiple of 8 elements");
+  const uint64_t esz = grad_dtype == DILOCO_F16 ? 2 : 4;
+  const uint64_t bytes = ((uint64_t)(ctx->cfg.k_workers - 1) * grad_stride + ctx->lay.n_pad) * esz;
+  return check_device_range(ctx, grads, bytes, "grads");
+}
+
+}  // namespace
+
+extern "C" {
+
+int diloco_query_layout(const diloco_config* cfg, diloco_layout* out, uint64_t* tensor_offsets) {
+  int rc = validate_problem(cfg);
+  if (rc != DILOCO_OK) return rc;
+  if (!out) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "layout output is NULL");
+  plan(cfg, out, tensor_offsets);
+  return DILOCO_OK;
+}
+
+int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco_ctx** out) {
+  if (!out) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "out is NULL");
+  int rc = validate_problem(cfg);
+  if (rc != DILOCO_OK) return rc;
+  rc = validate_hyper(cfg);
+  if (rc != DILOCO_OK) return rc;
+  if (!cfg->arena) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "arena is NULL");
+  if (((uintptr_t)cfg->arena & 255u) != 0)
+    return fail(nullptr, DILOCO_ERR_ALIGN, "arena must be 256-byte aligned");
+
+  diloco_ctx* c = new (std::nothrow) diloco_ctx();
+  if (!c) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "out of host memory");
+  c->cfg = *cfg;
+  c->numel.assign(cfg->numel, cfg->numel + cfg->n_tensors);
+  c->cfg.numel = c->numel.data();
+  c->offsets.resize(cfg->n_tensors);
+  plan(&c->cfg, &c->lay, c->offsets.data());
+  c->stream = (hipStream_t)cfg->stream;
+  c->d_state = nullptr;
+  c->parity = 0;
+  c->steps_since_outer = 0;
+  c->have_scale = false;
+  c->inv_scale = 1.0f;
+  c->checked_flags = nullptr;
+  c->checked_grads = nullptr;
+
+  auto bail = [&](int code) {
+    if (c->d_state) (void)hipFree(c->d_state);
+    g_err = c->err.empty() ? g_err : c->err;
+    delete c;
+    return code;
+  };
+
+  if (cfg->arena_bytes < c->lay.arena_bytes)
+    return bail(fail(c, DILOCO_ERR_ARENA_TOO_SMALL, "arena has %llu bytes, layout needs %llu",
+                     (unsigned long long)cfg->arena_bytes,
+                     (unsigned long long)c->lay.arena_bytes));
+
+  hipError_t e = hipGetDevice(&c->device);
+  if (e != hipSuccess) return bail(fail_hip(c, "hipGetDevice (no usable GPU runtime)", e));
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, c->device);
+  if (e != hipSuccess) return bail(fail_hip(c, "hipGetDeviceProperties", e));
+  c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+  rc = check_device_range(c, cfg->arena, c->lay.arena_bytes, "arena");
+  if (rc != DILOCO_OK) return bail(rc);
+
+  const uint32_t k = cfg->k_workers;
+  e = hipMalloc(reinterpret_cast<void**>(&c->d_state), 2 * k * sizeof(RepState));
+  if (e != hipSuccess) return bail(fail_hip(c, "hipMalloc(step state)", e));
+  std::vector<RepState> st(2 * k);
+  for (auto& s : st) { s.p1 = 1.0; s.p2 = 1.0; s.step = 0; s.pad = 0; }
+  e = hipMemcpyAsync(c->d_state, st.data(), st.size() * sizeof(RepState), hipMemcpyHostToDevice,
+                     c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);  // st is a host temporary
+  if (e != hipSuccess) return bail(fail_hip(c, "step state upload", e));
+
+  float* theta0 = buf(c, c->lay.off_theta0);
+  // Pack the caller's tensors into theta0, then clear the alignment gaps and the tail.
+  if (init_params) {
+    for (uint32_t t = 0; t < cfg->n_tensors; ++t) {
+      if (!init_params[t]) return bail(fail(c, DILOCO_ERR_INVALID_ARG, "init_params[%u] is NULL", t));
+      rc = check_device_range(c, init_params[t], c->numel[t] * 4, "init_params[t]");
+      if (rc != DILOCO_OK) return bail(rc);
+      e = hipMemcpyAsync(theta0 + c->offsets[t], init_params[t], c->numel[t] * 4,
+                         hipMemcpyDeviceToDevice, c->stream);
+      if (e != hipSuccess) return bail(fail_hip(c, "pack tensor into theta0", e));
+    }
+  }
+  for (uint32_t t = 0; t < cfg->n_tensors; ++t) {
+    const uint64_t end = c->offsets[t] + c->numel[t];
+    const uint64_t next = t + 1 < cfg->n_tensors ? c->offsets[t + 1] : c->lay.n_pad;
+    if (next > end) {
+      e = hipMemsetAsync(theta0 + end, 0, (next - end) * 4, c->stream);
+      if (e != hipSuccess) return bail(fail_hip(c, "clear padding", e));
+    }
+  }
+  e = launch_init_state(theta0, buf(c, c->lay.off_mom), buf(c, c->lay.off_theta),
+                        buf(c, c->lay.off_m), buf(c, c->lay.off_v), c->lay.stride, c->lay.n_pad,
+                        (int)k, c->stream);
+  if (e != hipSuccess) return bail(fail_hip(c, "init_state launch", e));
+  *out = c;
+  return DILOCO_OK;
+}
+
+int diloco_unscale_check(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
+                         int32_t grad_dtype, float inv_scale, int32_t* found_inf) {
+  if (!ctx) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "ctx is NULL");
+  int rc = check_grads(ctx, grads, grad_stride, grad_dtype);
+  if (rc != DILOCO_OK) return rc;
+  if (!found_inf) return fail(ctx, DILOCO_ERR_INVALID_ARG, "found_inf is NULL");
+  if (((uintptr_t)found_inf & 3u) != 0) return fail(ctx, DILOCO_ERR_ALIGN, "found_inf misaligned");
+  if (!std::isfinite(inv_scale) || !(inv_scale > 0.0f))
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "inv_scale must be finite and > 0");
+  rc = check_device_range(ctx, found_inf, ctx->cfg.k_workers * 4ull, "found_inf");
+  if (rc != DILOCO_OK) return rc;
+  hipError_t e = launch_check(grads, grad_stride, ctx->lay.n_pad, (int)ctx->cfg.k_workers,
+                              grad_dtype == DILOCO_F16, found_inf, ctx->tune, ctx->n_cu,
+                              ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, "unscale_check launch", e);
+  ctx->have_scale = true;
+  ctx->inv_scale = inv_scale;
+  ctx->checked_flags = found_inf;
+  ctx->checked_grads = grads;
+  return DILOCO_OK;
+}
+
+int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
+                      int32_t grad_dtype, double lr, const int32_t* found_inf) {
+  if (!ctx) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "ctx is NULL");
+  int rc = check_grads(ctx, grads, grad_stride, grad_dtype);
+  if (rc != DILOCO_OK) return rc;
+  if (lr < 0) lr = ctx->cfg.inner_lr;
+  if (!std::isfinite(lr)) return fail(ctx, DILOCO_ERR_INVALID_ARG, "lr must be finite");
+  float inv_scale = 1.0f;
+  if (found_inf) {
+    if (!ctx->have_scale || ctx->checked_flags != found_inf || ctx->checked_grads != grads)
+      return fail(ctx, DILOCO_ERR_STATE,
+                  "found_inf given without a preceding diloco_unscale_check of these gradients");
+    inv_scale = ctx->inv_scale;
+  }
+  const diloco_config& cf = ctx->cfg;
+  const uint32_t k = cf.k_workers;
+  InnerArgs a;
+  a.theta = buf(ctx, ctx->lay.off_theta);
+  a.m = buf(ctx, ctx->lay.off_m);
+  a.v = buf(ctx, ctx->lay.off_v);
+  a.g = grads;
+  a.stride = ctx->lay.stride;
+  a.g_stride = grad_stride;
+  a.n_pad = ctx->lay.n_pad;
+  a.found_inf = found_inf;
+  a.st_cur = ctx->d_state + (size_t)ctx->parity * k;
+  a.st_nxt = ctx->d_state + (size_t)(ctx->parity ^ 1) * k;
+  // Each scalar is formed in double and rounded to float once.
+  a.beta1d = cf.beta1;
+  a.beta2d = cf.beta2;
+  a.beta1 = (float)cf.beta1;
+  a.beta2 = (float)cf.beta2;
+  a.omb1 = (float)(1.0 - cf.beta1);
+  a.omb2 = (float)(1.0 - cf.beta2);
+  a.lr = (float)lr;
+  a.lr_wd = (float)(lr * cf.weight_decay);
+  a.eps = (float)cf.eps;
+  a.inv_scale = inv_scale;
+  hipError_t e = launch_inner(a, (int)k, grad_dtype == DILOCO_F16, ctx->tune, ctx->n_cu,
+                              ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, "inner step launch", e);
+  ctx->parity ^= 1;
+  ctx->have_scale = false;
+  ctx->steps_since_outer += 1;
+  if (cf.h_inner_steps != 0 && ctx->steps_since_outer % cf.h_inner_steps == 0)
+    return DILOCO_ROUND_COMPLETE;
+  return DILOCO_OK;
+}
+
+int diloco_outer_step(diloco_ctx* ctx) {
+  if (!ctx) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "ctx is NULL");
+  OuterArgs a;
+  a.theta0 = buf(ctx, ctx->lay.off_theta0);
+  a.mom = buf(ctx, ctx->lay.off_mom);
+  a.theta = buf(ctx, ctx->lay.off_theta);
+  a.stride = ctx->lay.stride;
+  a.n_pad = ctx->lay.n_pad;
+  a.lr = (float)ctx->cfg.outer_lr;
+  a.mu = (float)ctx->cfg.outer_momentum;
+  a.kf = (float)ctx->cfg.k_workers;
+  a.k = (int)ctx->cfg.k_workers;
+  a.f16 = ctx->cfg.pg_dtype == DILOCO_F16;
+  hipError_t e = launch_outer(a, ctx->tune, ctx->n_cu, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, "outer step launch", e);
+  ctx->steps_since_outer = 0;
+  return DILOCO_OK;
+}
+
+int diloco_get_buffer(diloco_ctx* ctx, int which, uint32_t replica, void** dev_ptr) {
+  if (!ctx || !dev_ptr) return fail(ctx, DILOCO_ERR_INVALID_ARG, "NULL argument");
+  if ((which == DILOCO_BUF_THETA || which == DILOCO_BUF_M || which == DILOCO_BUF_V) &&
+      replica >= ctx->cfg.k_workers)
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "replica %u out of range", replica);
+  const uint64_t rs = (uint64_t)replica * ctx->lay.stride;
+  switch (which) {
+    case DILOCO_BUF_THETA0: *dev_ptr = buf(ctx, ctx->lay.off_theta0); break;
+    case DILOCO_BUF_MOM: *dev_ptr = buf(ctx, ctx->lay.off_mom); break;
+    case DILOCO_BUF_THETA: *dev_ptr = buf(ctx, ctx->lay.off_theta) + rs; break;
+    case DILOCO_BUF_M: *dev_ptr = buf(ctx, ctx->lay.off_m) + rs; break;
+    case DILOCO_BUF_V: *dev_ptr = buf(ctx, ctx->lay.off_v) + rs; break;
+    default: return fail(ctx, DILOCO_ERR_INVALID_ARG, "unknown buffer selector %d", which);
+  }
+  return DILOCO_OK;
+}
+
+int diloco_get_layout(diloco_ctx* ctx, diloco_layout* out) {
+  if (!ctx || !out) return fail(ctx, DILOCO_ERR_INVALID_ARG, "NULL argument");
+  *out = ctx->lay;
+  return DILOCO_OK;
+}
+
+int diloco_get_steps(diloco_ctx* ctx, uint32_t* steps) {
+  if (!ctx || !steps) return fail(ctx, DILOCO_ERR_INVALID_ARG, "NULL argument");
+  const uint32_t k = ctx->cfg.k_workers;
+  std::vector<RepState> st(k);
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e == hipSuccess)
+    e = hipMemcpy(st.data(), ctx->d_state + (size_t)ctx->parity * k, k * sizeof(RepState),
+                  hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail_hip(ctx, "reading step counts", e);
+  for (uint32_t r = 0; r < k; ++r) steps[r] = (uint32_t)st[r].step;
+  return DILOCO_OK;
+}
+
+int diloco_cast_f32_to_f16(const float* in, uint16_t* out, uint64_t n, void* stream) {
+  if (n == 0) return DILOCO_OK;
+  if (!in || !out) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "NULL argument");
+  int rc = check_device_range(nullptr, in, n * 4, "in");
+  if (rc != DILOCO_OK) return rc;
+  rc = check_device_range(nullptr, out, n * 2, "out");
+  if (rc != DILOCO_OK) return rc;
+  hipError_t e = launch_cast(in, out, n, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(nullptr, "cast launch", e);
+  return DILOCO_OK;
+}
+
+int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value) {
+  if (!ctx || !name) return fail(ctx, DILOCO_ERR_INVALID_ARG, "NULL argument");
+  Tuning& t = ctx->tune;
+  auto is_vec = [](int v) { return v == 1 || v == 2 || v == 4 || v == 8; };
+  const std::string n(name);
+  if (n == "inner_vec" && is_vec(value)) t.inner_vec = value;
+  else if (n == "outer_vec" && (value == 1 || value == 2 || value == 4)) t.outer_vec = value;
+  else if (n == "inner_nt" && (value == 0 || value == 1)) t.inner_nt = value;
+  else if (n == "outer_nt" && (value == 0 || value == 1)) t.outer_nt = value;
+  else if (n == "inner_persist" && value >= 0 && value <= 64) t.inner_persist = value;
+  else if (n == "outer_persist" && value >= 0 && value <= 64) t.outer_persist = value;
+  else if (n == "check_persist" && value >= 0 && value <= 64) t.check_persist = value;
+  else if (n == "xcd_remap" && (value == 0 || value == 1)) t.xcd_remap = value;
+  else return fail(ctx, DILOCO_ERR_INVALID_ARG, "unknown tuning knob or value: %s=%d", name, value);
+  return DILOCO_OK;
+}
+
+const char* diloco_last_error(diloco_ctx* ctx) {
+  if (ctx) return ctx->err.c_str();
+  return g_err.c_str();
+}
+
+int diloco_destroy(diloco_ctx* ctx) {
+  if (!ctx) return DILOCO_OK;
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  hipError_t e2 = hipFree(ctx->d_state);
+  delete ctx;
+  if (e != hipSuccess) return fail_hip(nullptr, "stream synchronize at destroy", e);
+  if (e2 != hipSuccess) return fail_hip(nullptr, "hipFree at destroy", e2);
+  return DILOCO_OK;
+}
+
+}  // extern "C"

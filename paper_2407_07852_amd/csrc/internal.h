@@ -1,0 +1,65 @@
+// Internal interface between the C-ABI layer (api.hip) and the gfx950 kernels (kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace diloco {
+
+// Per-worker AdamW step state, kept on the device because skip decisions (found_inf) are
+// device-side.  p1 = beta1^t, p2 = beta2^t as running products in double.
+struct RepState {
+  double p1;
+  double p2;
+  int32_t step;
+  int32_t pad;
+};
+
+// Launch-shape knobs (see diloco_set_tuning).
+struct Tuning {
+  int inner_vec = 4;      // 128-bit vectors per thread per stream (1,2,4,8)
+  int inner_nt = 1;       // nontemporal loads/stores
+  int inner_persist = 0;  // 0: one tile per block; >0: that many blocks per CU, grid-stride
+  int outer_vec = 2;
+  int outer_nt = 1;
+  int outer_persist = 0;
+  int check_vec = 4;
+  int check_persist = 8;
+  int xcd_remap = 0;      // 1: give each of the 8 XCDs a contiguous range of tiles
+};
+
+struct InnerArgs {
+  float* theta;        // replica 0
+  float* m;
+  float* v;
+  const void* g;       // replica 0; float or binary16
+  uint64_t stride;     // elements between replicas of theta/m/v
+  uint64_t g_stride;   // elements between replicas of g
+  uint64_t n_pad;
+  const int32_t* found_inf;  // device, may be null
+  const RepState* st_cur;    // [k]
+  RepState* st_nxt;          // [k]
+  double beta1d, beta2d;
+  float beta1, beta2, omb1, omb2, lr, lr_wd, eps, inv_scale;
+};
+
+struct OuterArgs {
+  float* theta0;
+  float* mom;
+  float* theta;      // replica 0
+  uint64_t stride;
+  uint64_t n_pad;
+  float lr, mu, kf;
+  int k;
+  int f16;
+};
+
+hipError_t launch_inner(const InnerArgs& a, int k, bool g16, const Tuning& t, int n_cu,
+                        hipStream_t s);
+hipError_t launch_outer(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s);
+hipError_t launch_check(const void* g, uint64_t g_stride, uint64_t n_pad, int k, bool g16,
+                        int32_t* found_inf, const Tuning& t, int n_cu, hipStream_t s);
+hipError_t launch_init_state(float* theta0, float* mom, float* theta, float* m, float* v,
+                             uint64_t stride, uint64_t n_pad, int k, hipStream_t s);
+hipError_t launch_cast(const float* in, uint16_t* out, uint64_t n, hipStream_t s);
+
+}  // namespace diloco

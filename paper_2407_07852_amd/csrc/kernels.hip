@@ -1,0 +1,439 @@
+// gfx950 (MI355X, CDNA4) kernels of the DiLoCo optimizer hot path.
+//
+// Everything here is elementwise and HBM-bound, so the design is about memory streams, not
+// arithmetic: flat padded buffers, one 128-bit load/store per lane per access, every buffer
+// streamed exactly once per step, several independent vectors in flight per lane, and
+// nontemporal accesses because nothing is reused.  No MFMA: there is no contraction.
+//
+// Floating point follows the method's definition operation by operation: IEEE binary32,
+// round to nearest even, correctly rounded divide and sqrt, no fused multiply-add, no
+// flush-to-zero (build with -ffp-contract=off and without any fast-math option).
+#include "internal.h"
+
+#pragma clang fp contract(off)
+
+namespace diloco {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = 256;         // 4 wavefronts of 64 lanes
+constexpr int kVecElems = 4;        // floats per 128-bit access
+constexpr int kXcds = 8;
+
+template <bool NT, class T>
+__device__ __forceinline__ T ld(const T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT, class T>
+__device__ __forceinline__ void st(T* p, T x) {
+  if constexpr (NT) __builtin_nontemporal_store(x, p);
+  else *p = x;
+}
+
+// First tile of this block and the tile step of the grid-stride loop.  With xcd_remap the
+// hardware's round-robin of consecutive workgroups over the 8 XCDs is undone so that each XCD
+// walks one contiguous range of tiles (gridDim.x is then a multiple of 8).
+__device__ __forceinline__ uint32_t first_tile(bool xcd_remap) {
+  const uint32_t b = blockIdx.x;
+  if (!xcd_remap) return b;
+  return (b % kXcds) * (gridDim.x / kXcds) + b / kXcds;
+}
+
+// ------------------------------------------------------------------------------------------
+// Inner optimizer: AdamW over all k workers, grid = (tile blocks, k).
+// (Section "Implementation": the inner optimizer is AdamW, one step per training step.)
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void adamw_elem(float& th, float& m, float& v, float g,
+                                           const InnerArgs& a, float bc1, float bc2) {
+  const float mi = a.beta1 * m + a.omb1 * g;
+  const float vi = a.beta2 * v + a.omb2 * (g * g);
+  const float m_hat = mi / bc1;
+  const float v_hat = vi / bc2;
+  const float decayed = th - a.lr_wd * th;
+  th = decayed - a.lr * (m_hat / (sqrtf(v_hat) + a.eps));
+  m = mi;
+  v = vi;
+}
+
+template <int V, bool G16, bool NT>
+__global__ __launch_bounds__(kBlock) void adamw_flat_kernel(const InnerArgs a, uint32_t tiles,
+                                                            int xcd_remap) {
+  const uint32_t r = blockIdx.y;
+  // Worker r's step state.  A worker whose found_inf flag is set takes no step at all.
+  const bool skip = a.found_inf != nullptr && a.found_inf[r] != 0;
+  RepState rs = a.st_cur[r];
+  if (!skip) {
+    rs.p1 *= a.beta1d;
+    rs.p2 *= a.beta2d;
+    rs.step += 1;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) a.st_nxt[r] = rs;
+  if (skip) return;
+  const float bc1 = (float)(1.0 - rs.p1);  // 1 - beta1^t
+  const float bc2 = (float)(1.0 - rs.p2);  // 1 - beta2^t
+
+  f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta + (size_t)r * a.stride);
+  f32x4* __restrict__ m_p = reinterpret_cast<f32x4*>(a.m + (size_t)r * a.stride);
+  f32x4* __restrict__ v_p = reinterpret_cast<f32x4*>(a.v + (size_t)r * a.stride);
+  const f32x4* __restrict__ g32_p =
+      reinterpret_cast<const f32x4*>(static_cast<const float*>(a.g) + (size_t)r * a.g_stride);
+  const u32x2* __restrict__ g16_p =
+      reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(a.g) + (size_t)r * a.g_stride);
+
+  constexpr uint32_t kTileVecs = kBlock * V;
+  for (uint32_t tile = first_tile(xcd_remap); tile < tiles; tile += gridDim.x) {
+    const size_t base = (size_t)tile * kTileVecs + threadIdx.x;
+    f32x4 th[V], m[V], v[V], g[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      const size_t i = base + (size_t)j * kBlock;
+      if constexpr (G16) {
+        const u32x2 raw = ld<NT>(g16_p + i);
+        f16x4 h;
+        __builtin_memcpy(&h, &raw, 8);
+        g[j] = __builtin_convertvector(h, f32x4) * a.inv_scale;
+      } else {
+        g[j] = ld<NT>(g32_p + i);
+      }
+      th[j] = ld<NT>(th_p + i);
+      m[j] = ld<NT>(m_p + i);
+      v[j] = ld<NT>(v_p + i);
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+#pragma unroll
+      for (int c = 0; c < kVecElems; ++c) {
+        float t = th[j][c], mm = m[j][c], vv = v[j][c];
+        adamw_elem(t, mm, vv, g[j][c], a, bc1, bc2);
+        th[j][c] = t;
+        m[j][c] = mm;
+        v[j][c] = vv;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      const size_t i = base + (size_t)j * kBlock;
+      st<NT>(th_p + i, th[j]);
+      st<NT>(m_p + i, m[j]);
+      st<NT>(v_p + i, v[j]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Outer step (Figure 1), fused: pseudo-gradient, optional binary16 rounding, mean over the k
+// workers, Nesterov SGD on theta0, and the reset of every worker to the new theta0.
+// The pseudo-gradients never leave registers.
+// ------------------------------------------------------------------------------------------
+template <bool F16>
+__device__ __forceinline__ float pseudo_grad(float th0, float th_r) {
+  float d = th0 - th_r;
+  if constexpr (F16) d = (float)(_Float16)d;  // v_cvt_f16_f32 (RNE, subnormals kept) and back
+  return d;
+}
+
+__device__ __forceinline__ void nesterov_elem(float& th0, float& b, float dbar, float lr,
+                                              float mu) {
+  const float bn = mu * b + dbar;
+  th0 = th0 - lr * (dbar + mu * bn);
+  b = bn;
+}
+
+template <int K, int V, bool F16, bool NT>
+__global__ __launch_bounds__(kBlock) void outer_fused_kernel(const OuterArgs a, uint32_t tiles,
+                                                             int xcd_remap) {
+  f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
+  f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
+  f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
+  const size_t rstride = a.stride / kVecElems;  // replica stride in vectors
+  constexpr uint32_t kTileVecs = kBlock * V;
+  for (uint32_t tile = first_tile(xcd_remap); tile < tiles; tile += gridDim.x) {
+    const size_t base = (size_t)tile * kTileVecs + threadIdx.x;
+    f32x4 t0[V], b[V], th[K][V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      const size_t i = base + (size_t)j * kBlock;
+      t0[j] = ld<NT>(t0_p + i);
+      b[j] = ld<NT>(b_p + i);
+#pragma unroll
+      for (int r = 0; r < K; ++r) th[r][j] = ld<NT>(th_p + (size_t)r * rstride + i);
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+#pragma unroll
+      for (int c = 0; c < kVecElems; ++c) {
+        float s = pseudo_grad<F16>(t0[j][c], th[0][j][c]);
+#pragma unroll
+        for (int r = 1; r < K; ++r) s = s + pseudo_grad<F16>(t0[j][c], th[r][j][c]);
+        const float dbar = s / a.kf;
+        float t = t0[j][c], bb = b[j][c];
+        nesterov_elem(t, bb, dbar, a.lr, a.mu);
+        t0[j][c] = t;
+        b[j][c] = bb;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      const size_t i = base + (size_t)j * kBlock;
+      st<NT>(t0_p + i, t0[j]);
+      st<NT>(b_p + i, b[j]);
+#pragma unroll
+      for (int r = 0; r < K; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0[j]);
+    }
+  }
+}
+
+// Any k (run-time loop over the workers); one vector per thread.
+template <bool F16, bool NT>
+__global__ __launch_bounds__(kBlock) void outer_fused_anyk_kernel(const OuterArgs a,
+                                                                  uint32_t tiles) {
+  f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
+  f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
+  f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
+  const size_t rstride = a.stride / kVecElems;
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const size_t i = (size_t)tile * kBlock + threadIdx.x;
+    f32x4 t0 = ld<NT>(t0_p + i);
+    f32x4 b = ld<NT>(b_p + i);
+    f32x4 s;
+    {
+      const f32x4 th = ld<NT>(th_p + i);
+#pragma unroll
+      for (int c = 0; c < kVecElems; ++c) s[c] = pseudo_grad<F16>(t0[c], th[c]);
+    }
+    for (int r = 1; r < a.k; ++r) {
+      const f32x4 th = ld<NT>(th_p + (size_t)r * rstride + i);
+#pragma unroll
+      for (int c = 0; c < kVecElems; ++c) s[c] = s[c] + pseudo_grad<F16>(t0[c], th[c]);
+    }
+#pragma unroll
+    for (int c = 0; c < kVecElems; ++c) {
+      const float dbar = s[c] / a.kf;
+      float t = t0[c], bb = b[c];
+      nesterov_elem(t, bb, dbar, a.lr, a.mu);
+      t0[c] = t;
+      b[c] = bb;
+    }
+    st<NT>(t0_p + i, t0);
+    st<NT>(b_p + i, b);
+    for (int r = 0; r < a.k; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Gradient-scaler check: found_inf[r] = any element of worker r's gradient is inf or NaN.
+// Per lane a "bad" predicate; wave-level ballot; the four waves of a block meet in LDS; one
+// atomic per block, and only when something was found.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool nonfinite_f16x2(uint32_t w) {
+  const uint32_t e = w & 0x7c007c00u;
+  return (e & 0xffffu) == 0x7c00u || (e >> 16) == 0x7c00u;
+}
+__device__ __forceinline__ bool nonfinite_f32(uint32_t w) {
+  return (w & 0x7f800000u) == 0x7f800000u;
+}
+
+template <int V, bool G16>
+__global__ __launch_bounds__(kBlock) void unscale_check_kernel(const void* g, uint64_t g_stride,
+                                                               uint32_t tiles,
+                                                               int32_t* found_inf) {
+  const uint32_t r = blockIdx.y;
+  const size_t elem_bytes = G16 ? 2 : 4;
+  const u32x4* __restrict__ p = reinterpret_cast<const u32x4*>(
+      static_cast<const char*>(g) + (size_t)r * g_stride * elem_bytes);
+  constexpr uint32_t kTileVecs = kBlock * V;
+  bool bad = false;
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const size_t base = (size_t)tile * kTileVecs + threadIdx.x;
+    u32x4 w[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) w[j] = ld<true>(p + base + (size_t)j * kBlock);
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) bad |= G16 ? nonfinite_f16x2(w[j][c]) : nonfinite_f32(w[j][c]);
+    }
+  }
+  __shared__ int wave_bad[kBlock / 64];
+  const bool wave_any = __ballot(bad) != 0ull;
+  if ((threadIdx.x & 63) == 0) wave_bad[threadIdx.x >> 6] = wave_any ? 1 : 0;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int any = 0;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) any |= wave_bad[w];
+    if (any) atomicOr(found_inf + r, 1);
+  }
+}
+
+__global__ void zero_flags_kernel(int32_t* flags, int k) {
+  if ((int)threadIdx.x < k) flags[threadIdx.x] = 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// Starting state: every worker's weights = theta0, moments = 0, outer momentum = 0.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void init_state_kernel(const float* theta0, float* mom,
+                                                            float* theta, float* m, float* v,
+                                                            uint64_t stride, uint32_t tiles,
+                                                            int k) {
+  const f32x4* t0_p = reinterpret_cast<const f32x4*>(theta0);
+  const size_t rstride = stride / kVecElems;
+  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const size_t i = (size_t)tile * kBlock + threadIdx.x;
+    const f32x4 x = t0_p[i];
+    reinterpret_cast<f32x4*>(mom)[i] = zero;
+    for (int r = 0; r < k; ++r) {
+      reinterpret_cast<f32x4*>(theta)[(size_t)r * rstride + i] = x;
+      reinterpret_cast<f32x4*>(m)[(size_t)r * rstride + i] = zero;
+      reinterpret_cast<f32x4*>(v)[(size_t)r * rstride + i] = zero;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void cast_f16_kernel(const float* __restrict__ in,
+                                                          uint16_t* __restrict__ out,
+                                                          uint64_t n) {
+  const size_t step = (size_t)gridDim.x * kBlock;
+  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += step) {
+    const _Float16 h = (_Float16)in[i];
+    uint16_t bits;
+    __builtin_memcpy(&bits, &h, 2);
+    out[i] = bits;
+  }
+}
+
+// Grid size in x for `tiles` tiles: one block per tile, or persist*n_cu grid-stride blocks.
+uint32_t grid_x(uint64_t tiles, int persist, int n_cu, bool xcd_remap) {
+  uint64_t g = tiles;
+  if (persist > 0) {
+    const uint64_t cap = (uint64_t)persist * (uint64_t)n_cu;
+    if (g > cap) g = cap;
+  }
+  if (xcd_remap) g = (g + kXcds - 1) / kXcds * kXcds;
+  if (g == 0) g = 1;
+  return (uint32_t)g;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// Launchers.  n_pad is a multiple of 8192 elements, so every tile size below divides it.
+// ------------------------------------------------------------------------------------------
+template <int V, bool G16, bool NT>
+static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int n_cu,
+                                 hipStream_t s) {
+  const uint64_t tiles = a.n_pad / (uint64_t)(kBlock * kVecElems * V);
+  const dim3 grid(grid_x(tiles, t.inner_persist, n_cu, t.xcd_remap != 0), (uint32_t)k);
+  hipLaunchKernelGGL((adamw_flat_kernel<V, G16, NT>), grid, dim3(kBlock), 0, s, a,
+                     (uint32_t)tiles, t.xcd_remap);
+  return hipGetLastError();
+}
+
+template <bool G16, bool NT>
+static hipError_t launch_inner_v(const InnerArgs& a, int k, const Tuning& t, int n_cu,
+                                 hipStream_t s) {
+  switch (t.inner_vec) {
+    case 1: return launch_inner_t<1, G16, NT>(a, k, t, n_cu, s);
+    case 2: return launch_inner_t<2, G16, NT>(a, k, t, n_cu, s);
+    case 8: return launch_inner_t<8, G16, NT>(a, k, t, n_cu, s);
+    default: return launch_inner_t<4, G16, NT>(a, k, t, n_cu, s);
+  }
+}
+
+hipError_t launch_inner(const InnerArgs& a, int k, bool g16, const Tuning& t, int n_cu,
+                        hipStream_t s) {
+  if (g16) return t.inner_nt ? launch_inner_v<true, true>(a, k, t, n_cu, s)
+                             : launch_inner_v<true, false>(a, k, t, n_cu, s);
+  return t.inner_nt ? launch_inner_v<false, true>(a, k, t, n_cu, s)
+                    : launch_inner_v<false, false>(a, k, t, n_cu, s);
+}
+
+template <int K, int V, bool F16, bool NT>
+static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
+  const uint64_t tiles = a.n_pad / (uint64_t)(kBlock * kVecElems * V);
+  const dim3 grid(grid_x(tiles, t.outer_persist, n_cu, t.xcd_remap != 0));
+  hipLaunchKernelGGL((outer_fused_kernel<K, V, F16, NT>), grid, dim3(kBlock), 0, s, a,
+                     (uint32_t)tiles, t.xcd_remap);
+  return hipGetLastError();
+}
+
+template <int K, bool F16, bool NT>
+static hipError_t launch_outer_v(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
+  switch (t.outer_vec) {
+    case 1: return launch_outer_t<K, 1, F16, NT>(a, t, n_cu, s);
+    case 4: return launch_outer_t<K, (K <= 4 ? 4 : 2), F16, NT>(a, t, n_cu, s);
+    default: return launch_outer_t<K, 2, F16, NT>(a, t, n_cu, s);
+  }
+}
+
+template <bool F16, bool NT>
+static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
+  switch (a.k) {
+    case 1: return launch_outer_v<1, F16, NT>(a, t, n_cu, s);
+    case 2: return launch_outer_v<2, F16, NT>(a, t, n_cu, s);
+    case 3: return launch_outer_v<3, F16, NT>(a, t, n_cu, s);
+    case 4: return launch_outer_v<4, F16, NT>(a, t, n_cu, s);
+    case 5: return launch_outer_v<5, F16, NT>(a, t, n_cu, s);
+    case 6: return launch_outer_v<6, F16, NT>(a, t, n_cu, s);
+    case 7: return launch_outer_v<7, F16, NT>(a, t, n_cu, s);
+    case 8: return launch_outer_v<8, F16, NT>(a, t, n_cu, s);
+    default: {
+      const uint64_t tiles = a.n_pad / (uint64_t)(kBlock * kVecElems);
+      const dim3 grid(grid_x(tiles, t.outer_persist, n_cu, false));
+      hipLaunchKernelGGL((outer_fused_anyk_kernel<F16, NT>), grid, dim3(kBlock), 0, s, a,
+                         (uint32_t)tiles);
+      return hipGetLastError();
+    }
+  }
+}
+
+hipError_t launch_outer(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
+  if (a.f16) return t.outer_nt ? launch_outer_k<true, true>(a, t, n_cu, s)
+                               : launch_outer_k<true, false>(a, t, n_cu, s);
+  return t.outer_nt ? launch_outer_k<false, true>(a, t, n_cu, s)
+                    : launch_outer_k<false, false>(a, t, n_cu, s);
+}
+
+hipError_t launch_check(const void* g, uint64_t g_stride, uint64_t n_pad, int k, bool g16,
+                        int32_t* found_inf, const Tuning& t, int n_cu, hipStream_t s) {
+  hipLaunchKernelGGL(zero_flags_kernel, dim3(1), dim3(64), 0, s, found_inf, k);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  constexpr int V = 4;
+  const uint64_t vec_elems = g16 ? 8 : 4;
+  const uint64_t tiles = n_pad / (vec_elems * kBlock * V);
+  const dim3 grid(grid_x(tiles, t.check_persist, n_cu, false), (uint32_t)k);
+  if (g16)
+    hipLaunchKernelGGL((unscale_check_kernel<V, true>), grid, dim3(kBlock), 0, s, g, g_stride,
+                       (uint32_t)tiles, found_inf);
+  else
+    hipLaunchKernelGGL((unscale_check_kernel<V, false>), grid, dim3(kBlock), 0, s, g, g_stride,
+                       (uint32_t)tiles, found_inf);
+  return hipGetLastError();
+}
+
+hipError_t launch_init_state(float* theta0, float* mom, float* theta, float* m, float* v,
+                             uint64_t stride, uint64_t n_pad, int k, hipStream_t s) {
+  const uint64_t tiles = n_pad / (uint64_t)(kBlock * kVecElems);
+  const dim3 grid((uint32_t)(tiles < 65536 ? tiles : 65536));
+  hipLaunchKernelGGL(init_state_kernel, grid, dim3(kBlock), 0, s, theta0, mom, theta, m, v,
+                     stride, (uint32_t)tiles, k);
+  return hipGetLastError();
+}
+
+hipError_t launch_cast(const float* in, uint16_t* out, uint64_t n, hipStream_t s) {
+  uint64_t blocks = (n + kBlock - 1) / kBlock;
+  if (blocks > 65536) blocks = 65536;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(cast_f16_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, s, in, out, n);
+  return hipGetLastError();
+}
+
+}  // namespace diloco

@@ -1,0 +1,119 @@
+"""Shared test plumbing: builds the same seeded workload on both sides -- numpy arrays for the
+CPU oracle, device buffers for the HIP library -- and compares them.  No optimizer arithmetic
+lives here."""
+import numpy as np
+
+import oracle
+import synth
+
+PAPER_HP = dict(inner_lr=4e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.1,
+                outer_lr=0.7, outer_momentum=0.9)
+W_SIGMA, G_SIGMA = 0.02, 1e-3
+
+# spec tolerances
+STEP_RTOL, STEP_ATOL = 1e-6, 1e-7
+ROUND_RTOL = 1e-5
+
+
+def oracle_layout(wl):
+    return oracle.plan_layout(wl.numel, 64, 8192)
+
+
+class GpuSide:
+    """The HIP library on the workload, inputs generated on the device."""
+
+    def __init__(self, wl, k, pg_f16=False, hp=None, h=0):
+        import torch
+        import paper_2407_07852_amd as D
+        self.torch, self.D, self.wl, self.k = torch, D, wl, k
+        hp = dict(PAPER_HP if hp is None else hp)
+        self.kind = None
+
+        def fill(theta0, layout, offsets):
+            self.kind_np = wl.kind_map(offsets, layout.n_pad)
+            self.kind = torch.from_numpy(self.kind_np).to(theta0.device)
+            synth.device_fill_f32(theta0.data_ptr(), layout.n_pad, synth.key(synth.STREAM_WEIGHTS),
+                                  W_SIGMA, self.kind.data_ptr(), ones_as_one=True,
+                                  stream=torch.cuda.current_stream().cuda_stream)
+
+        self.dl = D.DiLoCo(wl.numel, k, fill_theta0=fill, h_inner_steps=h,
+                           pg_dtype=D.F16 if pg_f16 else D.F32, **hp)
+        self.n_pad = self.dl.layout.n_pad
+        self.grads = None
+
+    def gen_grads(self, step, f16=False, inject_replica=None, inject_period=0):
+        torch = self.torch
+        dt = torch.float16 if f16 else torch.float32
+        if self.grads is None or self.grads.dtype != dt:
+            self.grads = self.dl.new_grads(dt)
+        s = torch.cuda.current_stream().cuda_stream
+        for r in range(self.k):
+            key = synth.key(synth.STREAM_GRADS, r, step)
+            if f16:
+                inj = inject_replica is not None and r == inject_replica
+                synth.device_fill_f16(self.grads[r].data_ptr(), self.n_pad, key,
+                                      self.kind.data_ptr(),
+                                      inject_key=synth.key(synth.STREAM_NONFINITE) if inj else 0,
+                                      inject_period=inject_period if inj else 0, stream=s)
+            else:
+                synth.device_fill_f32(self.grads[r].data_ptr(), self.n_pad, key, G_SIGMA,
+                                      self.kind.data_ptr(), stream=s)
+        return self.grads
+
+    def host(self, t):
+        return t.detach().cpu().numpy()
+
+
+class CpuSide:
+    """The oracle on the same workload, inputs generated on the host."""
+
+    def __init__(self, wl, k, pg_f16=False, hp=None):
+        hp = dict(PAPER_HP if hp is None else hp)
+        self.wl, self.k = wl, k
+        self.offsets, self.n_pad = oracle_layout(wl)
+        self.kind = wl.kind_map(self.offsets, self.n_pad)
+        theta0 = synth.host_fill_f32(self.n_pad, synth.key(synth.STREAM_WEIGHTS), W_SIGMA,
+                                     self.kind, ones_as_one=True)
+        self.o = oracle.DiLoCoOracle(theta0, k, hp["inner_lr"], hp["beta1"], hp["beta2"],
+                                     hp["eps"], hp["weight_decay"], hp["outer_lr"],
+                                     hp["outer_momentum"], pg_f16)
+
+    def gen_grads(self, step, f16=False, inject_replica=None, inject_period=0):
+        out = []
+        for r in range(self.k):
+            key = synth.key(synth.STREAM_GRADS, r, step)
+            if f16:
+                inj = inject_replica is not None and r == inject_replica
+                out.append(synth.host_fill_f16(
+                    self.n_pad, key, self.kind,
+                    inject_key=synth.key(synth.STREAM_NONFINITE) if inj else 0,
+                    inject_period=inject_period if inj else 0))
+            else:
+                out.append(synth.host_fill_f32(self.n_pad, key, G_SIGMA, self.kind))
+        return out
+
+
+def compare(name, got, want, rtol, atol):
+    """Element-by-element comparison; returns the number of bitwise mismatches."""
+    got = np.asarray(got).reshape(-1)
+    want = np.asarray(want).reshape(-1)
+    assert got.shape == want.shape, (name, got.shape, want.shape)
+    nan_w, nan_g = np.isnan(want), np.isnan(got)
+    assert np.array_equal(nan_w, nan_g), name + ": NaN positions differ"
+    ok = np.isclose(got, want, rtol=rtol, atol=atol, equal_nan=True)
+    if not ok.all():
+        i = int(np.argmin(ok))
+        raise AssertionError("%s: %d of %d outside tolerance; first at %d: got %r want %r"
+                             % (name, int((~ok).sum()), got.size, i, got[i], want[i]))
+    return int((got.view(np.uint32) != want.view(np.uint32))[~nan_w].sum())
+
+
+def compare_state(gpu, cpu, rtol=STEP_RTOL, atol=STEP_ATOL, what=("theta", "m", "v")):
+    """Full-array comparison of every worker's state; returns total bitwise mismatches."""
+    mism = 0
+    for r in range(gpu.k):
+        w = cpu.o.workers[r]
+        for name in what:
+            mism += compare("%s[%d]" % (name, r), gpu.host(getattr(gpu.dl, name)[r]),
+                            getattr(w, name), rtol, atol)
+    return mism
