@@ -12,7 +12,8 @@
  * Here all k replicas live on ONE GPU in a single caller-owned arena of flat, padded
  * multi-tensor buffers, and each step is one fused streaming kernel:
  *
- *   arena (FP32):  theta0[n_pad]  mom[n_pad]  theta[k][stride]  m[k][stride]  v[k][stride]
+ *   arena (FP32):  theta0[stride]  mom[stride]  theta[k][stride]  m[k][stride]  v[k][stride]
+ *   (n_pad <= stride elements of each buffer are used)
  *
  * theta0 = outer weights theta(t); mom = outer momentum buffer; theta/m/v = each worker's
  * weights and AdamW moments.  Every tensor of the parameter list starts at a multiple of 64
@@ -64,6 +65,7 @@ enum { /* diloco_get_buffer selector */
 #define DILOCO_MAX_WORKERS 64
 #define DILOCO_TENSOR_ALIGN 64u /* elements: every tensor starts on a 256-byte boundary */
 #define DILOCO_TILE 8192u       /* elements: n_pad is a multiple of this */
+#define DILOCO_STRIDE_ALIGN_BYTES 2097152u /* stride*4 is a multiple of this (2 MiB) */
 
 /* Problem statement: the parameter tensor list, the two optimizers' hyper-parameters
  * (Appendix A, Table 3 gives inner lr 4e-4, weight decay 0.1, outer lr 0.7, outer momentum

@@ -197,8 +197,11 @@ class DiLoCo:
         return torch.as_strided(flat, (reps, L.n_pad), (L.stride, 1))
 
     def new_grads(self, dtype=torch.float32):
-        """A zeroed gradient buffer [k][n_pad] of the given dtype."""
-        return torch.zeros((self.k, self.layout.n_pad), dtype=dtype, device=self.device)
+        """A zeroed gradient buffer [k][n_pad] of the given dtype, replicas spaced like the
+        arena's (stride elements apart) so that all streams of a tile share their alignment."""
+        L = self.layout
+        flat = torch.zeros((self.k - 1) * L.stride + L.n_pad, dtype=dtype, device=self.device)
+        return torch.as_strided(flat, (self.k, L.n_pad), (L.stride, 1))
 
     def new_flags(self):
         return torch.zeros(self.k, dtype=torch.int32, device=self.device)

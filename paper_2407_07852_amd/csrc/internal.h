@@ -16,14 +16,14 @@ struct RepState {
 
 // Launch-shape knobs (see diloco_set_tuning).
 struct Tuning {
-  int inner_vec = 4;      // 128-bit vectors per thread per stream (1,2,4,8)
+  int inner_block = 64;   // threads per workgroup (64, 128, 256)
+  int inner_vec = 1;      // 128-bit vectors per thread per stream (1, 2, 4)
   int inner_nt = 1;       // nontemporal loads/stores
-  int inner_persist = 0;  // 0: one tile per block; >0: that many blocks per CU, grid-stride
-  int outer_vec = 2;
+  int outer_block = 64;   // 64 or 256
+  int outer_vec = 1;      // 1 or 2
   int outer_nt = 1;
-  int outer_persist = 0;
   int check_vec = 4;
-  int check_persist = 8;
+  int check_persist = 8;  // inf/NaN check: grid-stride blocks per CU (0: one tile per block)
   int xcd_remap = 0;      // 1: give each of the 8 XCDs a contiguous range of tiles
 };
 

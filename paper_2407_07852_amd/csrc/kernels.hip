@@ -35,10 +35,12 @@ __device__ __forceinline__ void st(T* p, T x) {
   else *p = x;
 }
 
-// First tile of this block and the tile step of the grid-stride loop.  With xcd_remap the
-// hardware's round-robin of consecutive workgroups over the 8 XCDs is undone so that each XCD
-// walks one contiguous range of tiles (gridDim.x is then a multiple of 8).
-__device__ __forceinline__ uint32_t first_tile(bool xcd_remap) {
+// Tile handled by this workgroup (one tile per workgroup: many small workgroups in dispatch
+// order keep every stream's in-flight addresses in a tight window, which measured faster than
+// any grid-stride variant).  With xcd_remap the hardware's round-robin of consecutive
+// workgroups over the 8 XCDs is undone so that each XCD walks one contiguous range of tiles
+// (gridDim.x is then a multiple of 8 and may exceed the tile count).
+__device__ __forceinline__ uint32_t tile_of_block(int xcd_remap) {
   const uint32_t b = blockIdx.x;
   if (!xcd_remap) return b;
   return (b % kXcds) * (gridDim.x / kXcds) + b / kXcds;
@@ -60,11 +62,38 @@ __device__ __forceinline__ void adamw_elem(float& th, float& m, float& v, float 
   v = vi;
 }
 
-template <int V, bool G16, bool NT>
-__global__ __launch_bounds__(kBlock) void adamw_flat_kernel(const InnerArgs a, uint32_t tiles,
-                                                            int xcd_remap) {
+template <int B, int V, bool G16, bool NT>
+__global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32_t tiles,
+                                                       int xcd_remap) {
   const uint32_t r = blockIdx.y;
-  // Worker r's step state.  A worker whose found_inf flag is set takes no step at all.
+  const uint32_t tile = tile_of_block(xcd_remap);
+  if (tile >= tiles) return;
+
+  f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta + (size_t)r * a.stride);
+  f32x4* __restrict__ m_p = reinterpret_cast<f32x4*>(a.m + (size_t)r * a.stride);
+  f32x4* __restrict__ v_p = reinterpret_cast<f32x4*>(a.v + (size_t)r * a.stride);
+  const f32x4* __restrict__ g32_p =
+      reinterpret_cast<const f32x4*>(static_cast<const float*>(a.g) + (size_t)r * a.g_stride);
+  const u32x2* __restrict__ g16_p =
+      reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(a.g) + (size_t)r * a.g_stride);
+
+  // The tile's loads are issued before the worker's step state is read, so that the state's
+  // dependent scalar loads overlap the HBM latency instead of preceding it.
+  const size_t base = (size_t)tile * (B * V) + threadIdx.x;
+  f32x4 th[V], m[V], v[V], g[V];
+  u32x2 graw[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    const size_t i = base + (size_t)j * B;
+    if constexpr (G16) graw[j] = ld<NT>(g16_p + i);
+    else g[j] = ld<NT>(g32_p + i);
+    th[j] = ld<NT>(th_p + i);
+    m[j] = ld<NT>(m_p + i);
+    v[j] = ld<NT>(v_p + i);
+  }
+
+  // Worker r's step state.  A worker whose found_inf flag is set takes no step at all: its
+  // weights, moments and step count stay as they are.
   const bool skip = a.found_inf != nullptr && a.found_inf[r] != 0;
   RepState rs = a.st_cur[r];
   if (!skip) {
@@ -77,51 +106,28 @@ __global__ __launch_bounds__(kBlock) void adamw_flat_kernel(const InnerArgs a, u
   const float bc1 = (float)(1.0 - rs.p1);  // 1 - beta1^t
   const float bc2 = (float)(1.0 - rs.p2);  // 1 - beta2^t
 
-  f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta + (size_t)r * a.stride);
-  f32x4* __restrict__ m_p = reinterpret_cast<f32x4*>(a.m + (size_t)r * a.stride);
-  f32x4* __restrict__ v_p = reinterpret_cast<f32x4*>(a.v + (size_t)r * a.stride);
-  const f32x4* __restrict__ g32_p =
-      reinterpret_cast<const f32x4*>(static_cast<const float*>(a.g) + (size_t)r * a.g_stride);
-  const u32x2* __restrict__ g16_p =
-      reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(a.g) + (size_t)r * a.g_stride);
-
-  constexpr uint32_t kTileVecs = kBlock * V;
-  for (uint32_t tile = first_tile(xcd_remap); tile < tiles; tile += gridDim.x) {
-    const size_t base = (size_t)tile * kTileVecs + threadIdx.x;
-    f32x4 th[V], m[V], v[V], g[V];
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-      const size_t i = base + (size_t)j * kBlock;
-      if constexpr (G16) {
-        const u32x2 raw = ld<NT>(g16_p + i);
-        f16x4 h;
-        __builtin_memcpy(&h, &raw, 8);
-        g[j] = __builtin_convertvector(h, f32x4) * a.inv_scale;
-      } else {
-        g[j] = ld<NT>(g32_p + i);
-      }
-      th[j] = ld<NT>(th_p + i);
-      m[j] = ld<NT>(m_p + i);
-      v[j] = ld<NT>(v_p + i);
+  for (int j = 0; j < V; ++j) {
+    if constexpr (G16) {
+      f16x4 h;
+      __builtin_memcpy(&h, &graw[j], 8);
+      g[j] = __builtin_convertvector(h, f32x4) * a.inv_scale;
     }
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-#pragma unroll
-      for (int c = 0; c < kVecElems; ++c) {
-        float t = th[j][c], mm = m[j][c], vv = v[j][c];
-        adamw_elem(t, mm, vv, g[j][c], a, bc1, bc2);
-        th[j][c] = t;
-        m[j][c] = mm;
-        v[j][c] = vv;
-      }
+    for (int c = 0; c < kVecElems; ++c) {
+      float t = th[j][c], mm = m[j][c], vv = v[j][c];
+      adamw_elem(t, mm, vv, g[j][c], a, bc1, bc2);
+      th[j][c] = t;
+      m[j][c] = mm;
+      v[j][c] = vv;
     }
+  }
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-      const size_t i = base + (size_t)j * kBlock;
-      st<NT>(th_p + i, th[j]);
-      st<NT>(m_p + i, m[j]);
-      st<NT>(v_p + i, v[j]);
-    }
+  for (int j = 0; j < V; ++j) {
+    const size_t i = base + (size_t)j * B;
+    st<NT>(th_p + i, th[j]);
+    st<NT>(m_p + i, m[j]);
+    st<NT>(v_p + i, v[j]);
   }
 }
 
@@ -144,47 +150,46 @@ __device__ __forceinline__ void nesterov_elem(float& th0, float& b, float dbar, 
   b = bn;
 }
 
-template <int K, int V, bool F16, bool NT>
-__global__ __launch_bounds__(kBlock) void outer_fused_kernel(const OuterArgs a, uint32_t tiles,
-                                                             int xcd_remap) {
+template <int B, int K, int V, bool F16, bool NT>
+__global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint32_t tiles,
+                                                        int xcd_remap) {
+  const uint32_t tile = tile_of_block(xcd_remap);
+  if (tile >= tiles) return;
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
   const size_t rstride = a.stride / kVecElems;  // replica stride in vectors
-  constexpr uint32_t kTileVecs = kBlock * V;
-  for (uint32_t tile = first_tile(xcd_remap); tile < tiles; tile += gridDim.x) {
-    const size_t base = (size_t)tile * kTileVecs + threadIdx.x;
-    f32x4 t0[V], b[V], th[K][V];
+  const size_t base = (size_t)tile * (B * V) + threadIdx.x;
+  f32x4 t0[V], b[V], th[K][V];
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-      const size_t i = base + (size_t)j * kBlock;
-      t0[j] = ld<NT>(t0_p + i);
-      b[j] = ld<NT>(b_p + i);
+  for (int j = 0; j < V; ++j) {
+    const size_t i = base + (size_t)j * B;
+    t0[j] = ld<NT>(t0_p + i);
+    b[j] = ld<NT>(b_p + i);
 #pragma unroll
-      for (int r = 0; r < K; ++r) th[r][j] = ld<NT>(th_p + (size_t)r * rstride + i);
+    for (int r = 0; r < K; ++r) th[r][j] = ld<NT>(th_p + (size_t)r * rstride + i);
+  }
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+#pragma unroll
+    for (int c = 0; c < kVecElems; ++c) {
+      float s = pseudo_grad<F16>(t0[j][c], th[0][j][c]);
+#pragma unroll
+      for (int r = 1; r < K; ++r) s = s + pseudo_grad<F16>(t0[j][c], th[r][j][c]);
+      const float dbar = s / a.kf;
+      float t = t0[j][c], bb = b[j][c];
+      nesterov_elem(t, bb, dbar, a.lr, a.mu);
+      t0[j][c] = t;
+      b[j][c] = bb;
     }
+  }
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
+  for (int j = 0; j < V; ++j) {
+    const size_t i = base + (size_t)j * B;
+    st<NT>(t0_p + i, t0[j]);
+    st<NT>(b_p + i, b[j]);
 #pragma unroll
-      for (int c = 0; c < kVecElems; ++c) {
-        float s = pseudo_grad<F16>(t0[j][c], th[0][j][c]);
-#pragma unroll
-        for (int r = 1; r < K; ++r) s = s + pseudo_grad<F16>(t0[j][c], th[r][j][c]);
-        const float dbar = s / a.kf;
-        float t = t0[j][c], bb = b[j][c];
-        nesterov_elem(t, bb, dbar, a.lr, a.mu);
-        t0[j][c] = t;
-        b[j][c] = bb;
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < V; ++j) {
-      const size_t i = base + (size_t)j * kBlock;
-      st<NT>(t0_p + i, t0[j]);
-      st<NT>(b_p + i, b[j]);
-#pragma unroll
-      for (int r = 0; r < K; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0[j]);
-    }
+    for (int r = 0; r < K; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0[j]);
   }
 }
 
@@ -326,24 +331,33 @@ uint32_t grid_x(uint64_t tiles, int persist, int n_cu, bool xcd_remap) {
 // ------------------------------------------------------------------------------------------
 // Launchers.  n_pad is a multiple of 8192 elements, so every tile size below divides it.
 // ------------------------------------------------------------------------------------------
-template <int V, bool G16, bool NT>
+template <int B, int V, bool G16, bool NT>
 static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int n_cu,
                                  hipStream_t s) {
-  const uint64_t tiles = a.n_pad / (uint64_t)(kBlock * kVecElems * V);
-  const dim3 grid(grid_x(tiles, t.inner_persist, n_cu, t.xcd_remap != 0), (uint32_t)k);
-  hipLaunchKernelGGL((adamw_flat_kernel<V, G16, NT>), grid, dim3(kBlock), 0, s, a,
+  const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
+  const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0), (uint32_t)k);
+  hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT>), grid, dim3(B), 0, s, a,
                      (uint32_t)tiles, t.xcd_remap);
   return hipGetLastError();
+}
+
+template <int B, bool G16, bool NT>
+static hipError_t launch_inner_b(const InnerArgs& a, int k, const Tuning& t, int n_cu,
+                                 hipStream_t s) {
+  switch (t.inner_vec) {
+    case 2: return launch_inner_t<B, 2, G16, NT>(a, k, t, n_cu, s);
+    case 4: return launch_inner_t<B, 4, G16, NT>(a, k, t, n_cu, s);
+    default: return launch_inner_t<B, 1, G16, NT>(a, k, t, n_cu, s);
+  }
 }
 
 template <bool G16, bool NT>
 static hipError_t launch_inner_v(const InnerArgs& a, int k, const Tuning& t, int n_cu,
                                  hipStream_t s) {
-  switch (t.inner_vec) {
-    case 1: return launch_inner_t<1, G16, NT>(a, k, t, n_cu, s);
-    case 2: return launch_inner_t<2, G16, NT>(a, k, t, n_cu, s);
-    case 8: return launch_inner_t<8, G16, NT>(a, k, t, n_cu, s);
-    default: return launch_inner_t<4, G16, NT>(a, k, t, n_cu, s);
+  switch (t.inner_block) {
+    case 128: return launch_inner_b<128, G16, NT>(a, k, t, n_cu, s);
+    case 256: return launch_inner_b<256, G16, NT>(a, k, t, n_cu, s);
+    default: return launch_inner_b<64, G16, NT>(a, k, t, n_cu, s);
   }
 }
 
@@ -355,22 +369,22 @@ hipError_t launch_inner(const InnerArgs& a, int k, bool g16, const Tuning& t, in
                     : launch_inner_v<false, false>(a, k, t, n_cu, s);
 }
 
-template <int K, int V, bool F16, bool NT>
+template <int B, int K, int V, bool F16, bool NT>
 static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
-  const uint64_t tiles = a.n_pad / (uint64_t)(kBlock * kVecElems * V);
-  const dim3 grid(grid_x(tiles, t.outer_persist, n_cu, t.xcd_remap != 0));
-  hipLaunchKernelGGL((outer_fused_kernel<K, V, F16, NT>), grid, dim3(kBlock), 0, s, a,
+  const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
+  const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0));
+  hipLaunchKernelGGL((outer_fused_kernel<B, K, V, F16, NT>), grid, dim3(B), 0, s, a,
                      (uint32_t)tiles, t.xcd_remap);
   return hipGetLastError();
 }
 
 template <int K, bool F16, bool NT>
 static hipError_t launch_outer_v(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
-  switch (t.outer_vec) {
-    case 1: return launch_outer_t<K, 1, F16, NT>(a, t, n_cu, s);
-    case 4: return launch_outer_t<K, (K <= 4 ? 4 : 2), F16, NT>(a, t, n_cu, s);
-    default: return launch_outer_t<K, 2, F16, NT>(a, t, n_cu, s);
-  }
+  if (t.outer_block == 256)
+    return t.outer_vec == 2 ? launch_outer_t<256, K, 2, F16, NT>(a, t, n_cu, s)
+                            : launch_outer_t<256, K, 1, F16, NT>(a, t, n_cu, s);
+  return t.outer_vec == 2 ? launch_outer_t<64, K, 2, F16, NT>(a, t, n_cu, s)
+                          : launch_outer_t<64, K, 1, F16, NT>(a, t, n_cu, s);
 }
 
 template <bool F16, bool NT>
@@ -386,7 +400,7 @@ static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, int n_cu, 
     case 8: return launch_outer_v<8, F16, NT>(a, t, n_cu, s);
     default: {
       const uint64_t tiles = a.n_pad / (uint64_t)(kBlock * kVecElems);
-      const dim3 grid(grid_x(tiles, t.outer_persist, n_cu, false));
+      const dim3 grid(grid_x(tiles, 16, n_cu, false));
       hipLaunchKernelGGL((outer_fused_anyk_kernel<F16, NT>), grid, dim3(kBlock), 0, s, a,
                          (uint32_t)tiles);
       return hipGetLastError();

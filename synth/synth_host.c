@@ -20,6 +20,7 @@ void synth_host_fill_f32(float* out, const uint8_t* kind, uint64_t first, size_t
 /* Same values at an arbitrary list of flat indices; kind_at[j] is the kind of idx[j]. */
 void synth_host_gather_f32(float* out, const uint8_t* kind_at, const uint64_t* idx, size_t n_idx,
                            uint64_t key, float c, int ones_as_one) {
+#pragma omp parallel for schedule(static)
   for (size_t j = 0; j < n_idx; ++j) {
     const uint8_t kd = kind_at ? kind_at[j] : SYNTH_KIND_NORMAL;
     float x = 0.0f;
@@ -51,6 +52,7 @@ void synth_host_fill_f16(uint16_t* out, const uint8_t* kind, uint64_t first, siz
 void synth_host_gather_f16(uint16_t* out, const uint8_t* kind_at, const uint64_t* idx,
                            size_t n_idx, uint64_t key, uint64_t inject_key,
                            uint32_t inject_period) {
+#pragma omp parallel for schedule(static)
   for (size_t j = 0; j < n_idx; ++j) {
     const uint8_t kd = kind_at ? kind_at[j] : SYNTH_KIND_NORMAL;
     uint16_t h = 0;

@@ -117,3 +117,48 @@ def compare_state(gpu, cpu, rtol=STEP_RTOL, atol=STEP_ATOL, what=("theta", "m", 
             mism += compare("%s[%d]" % (name, r), gpu.host(getattr(gpu.dl, name)[r]),
                             getattr(w, name), rtol, atol)
     return mism
+
+
+# ---------------------------------------------------------------- sampled parity (large sets)
+def sample_indices(wl, offsets, n_pad, every=4099, edge=64):
+    """First/last `edge` elements of every tensor, every pad element next to a tensor, every
+    `every`-th flat index.  The path is elementwise, so the oracle run on these indices alone
+    equals the oracle run on everything (pinned by test_elementwise_independence)."""
+    parts = [np.arange(0, n_pad, every, dtype=np.int64)]
+    for off, n in zip(offsets, wl.numel):
+        off, n = int(off), int(n)
+        parts.append(np.arange(off, off + min(edge, n)))
+        parts.append(np.arange(off + max(0, n - edge), off + n))
+        parts.append(np.arange(off + n, min(n_pad, (off + n + 63) // 64 * 64)))   # gap after it
+    parts.append(np.arange(max(0, n_pad - edge), n_pad))
+    return np.unique(np.concatenate(parts))
+
+
+class SampledCpuSide:
+    """The oracle restricted to a set of flat indices."""
+
+    def __init__(self, wl, k, idx, pg_f16=False, hp=None):
+        hp = dict(PAPER_HP if hp is None else hp)
+        self.k, self.idx = k, np.ascontiguousarray(idx, dtype=np.uint64)
+        offsets, n_pad = oracle_layout(wl)
+        self.offsets, self.n_pad = offsets, n_pad
+        # kind of each sampled index, without building the whole map
+        ends = offsets + wl.numel
+        t = np.searchsorted(offsets, self.idx, side="right") - 1
+        inside = self.idx < ends[t]
+        self.kind_at = np.where(inside, np.where(wl.is_vector[t], synth.KIND_ONE,
+                                                 synth.KIND_NORMAL), synth.KIND_PAD).astype(np.uint8)
+        theta0 = synth.host_gather_f32(self.idx, synth.key(synth.STREAM_WEIGHTS), W_SIGMA,
+                                       self.kind_at, ones_as_one=True)
+        self.o = oracle.DiLoCoOracle(theta0, k, hp["inner_lr"], hp["beta1"], hp["beta2"],
+                                     hp["eps"], hp["weight_decay"], hp["outer_lr"],
+                                     hp["outer_momentum"], pg_f16)
+
+    def gen_grads(self, step):
+        return [synth.host_gather_f32(self.idx, synth.key(synth.STREAM_GRADS, r, step), G_SIGMA,
+                                      self.kind_at) for r in range(self.k)]
+
+
+def gather_gpu(gpu, t, idx_dev):
+    """Rows of a [reps][n_pad] device view at the sampled flat indices, on the host."""
+    return gpu.torch.index_select(t, t.dim() - 1, idx_dev).cpu().numpy()

@@ -1,0 +1,137 @@
+"""CPU-only checks of the product side: the shared library loads and exports every symbol the
+header declares, the host-side layout planner agrees with the oracle's independent planner,
+argument validation rejects bad problems without touching a GPU, and the input generator's
+host twin matches a pure-Python restatement of its hash."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _D():
+    import paper_2407_07852_amd as D
+    return D
+
+
+def test_library_exports_every_declared_symbol():
+    D = _D()
+    header = open(os.path.join(ROOT, "include", "diloco.h")).read()
+    declared = sorted(set(re.findall(r"\b(diloco_[a-z0-9_]+)\s*\(", header)))
+    assert len(declared) >= 12 and set(declared) == set(D.binding.EXPORTS)
+    L = ctypes.CDLL(D.binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_header_constants_match_binding():
+    D = _D()
+    header = open(os.path.join(ROOT, "include", "diloco.h")).read()
+    for name, val in (("DILOCO_MAX_WORKERS", D.MAX_WORKERS), ("DILOCO_TENSOR_ALIGN", D.TENSOR_ALIGN),
+                      ("DILOCO_TILE", D.TILE)):
+        assert int(re.search(name + r"\s+(\d+)", header).group(1)) == val
+    for name in ("OK", "ROUND_COMPLETE", "ERR_INVALID_ARG", "ERR_ALIGN", "ERR_ARENA_TOO_SMALL",
+                 "ERR_HIP", "ERR_STATE"):
+        assert int(re.search(r"DILOCO_" + name + r"\s*=\s*(-?\d+)", header).group(1)) == getattr(D, name)
+
+
+def test_layout_agrees_with_oracle_planner():
+    D = _D()
+    rng = np.random.default_rng(0)
+    cases = [synth.tiny().numel, synth.llama_150m().numel, synth.llama_1_1b().numel,
+             synth.stress().numel, np.array([1], dtype=np.uint64)]
+    for _ in range(50):
+        cases.append(rng.integers(1, 20000, size=int(rng.integers(1, 60))).astype(np.uint64))
+    for numel in cases:
+        k = int(rng.integers(1, 9))
+        lay, offs = D.diloco_query_layout(D.make_config(numel, k))
+        want_off, want_pad = oracle.plan_layout(numel, D.TENSOR_ALIGN, D.TILE)
+        assert offs == [int(o) for o in want_off] and lay.n_pad == want_pad
+        assert lay.stride >= lay.n_pad and (lay.stride * 4) % (2 << 20) == 0
+        assert lay.stride - lay.n_pad < (2 << 20) // 4
+        # buffers in order, none overlapping, arena covers the last one
+        starts = [lay.off_theta0, lay.off_mom, lay.off_theta, lay.off_m, lay.off_v]
+        sizes = [lay.stride * 4, lay.stride * 4] + [k * lay.stride * 4] * 3
+        for i in range(4):
+            assert starts[i] + sizes[i] <= starts[i + 1]
+        assert starts[4] + sizes[4] <= lay.arena_bytes
+        assert all(s % 256 == 0 for s in starts)
+
+
+def test_known_workload_sizes():
+    assert synth.tiny().n_params == 787456
+    assert synth.llama_150m().n_params == 234119168 and len(synth.llama_150m().shapes) == 109
+    assert synth.llama_1_1b().n_params == 1100046336 and len(synth.llama_1_1b().shapes) == 200
+    st = synth.stress()
+    assert len(st.shapes) == 2109 and all(1 <= int(n) <= 4096 for n in st.numel[109:])
+
+
+def test_bad_problems_are_rejected_on_the_host():
+    D = _D()
+
+    def code(cfg, init=False):
+        with pytest.raises(D.DilocoError) as e:
+            D.diloco_init(cfg) if init else D.diloco_query_layout(cfg)
+        return e.value.code
+
+    assert code(D.make_config([], 2)) == D.ERR_INVALID_ARG
+    assert code(D.make_config([4, 0, 3], 2)) == D.ERR_INVALID_ARG
+    assert code(D.make_config([4], 0)) == D.ERR_INVALID_ARG
+    assert code(D.make_config([4], D.MAX_WORKERS + 1)) == D.ERR_INVALID_ARG
+    assert "k_workers" in D.diloco_last_error()
+    for bad in (dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0), dict(inner_lr=-1.0),
+                dict(inner_lr=float("nan")), dict(weight_decay=-1.0), dict(outer_momentum=1.0),
+                dict(outer_lr=float("inf")), dict(pg_dtype=5)):
+        assert code(D.make_config([4], 2, arena=256, arena_bytes=1 << 30, **bad), init=True) \
+            == D.ERR_INVALID_ARG, bad
+    assert code(D.make_config([4], 2, arena=None, arena_bytes=1 << 30), init=True) == D.ERR_INVALID_ARG
+    assert code(D.make_config([4], 2, arena=264, arena_bytes=1 << 30), init=True) == D.ERR_ALIGN
+    assert code(D.make_config([4], 2, arena=256, arena_bytes=16), init=True) == D.ERR_ARENA_TOO_SMALL
+
+
+def test_no_gpu_means_a_loud_error_not_a_fallback():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    D = _D()
+    with pytest.raises(D.DilocoError) as e:
+        D.diloco_init(D.make_config([4], 2, arena=256, arena_bytes=1 << 30))
+    assert e.value.code == D.ERR_HIP
+
+
+def _mix64(z):
+    M = (1 << 64) - 1
+    z ^= z >> 30
+    z = (z * 0xBF58476D1CE4E5B9) & M
+    z ^= z >> 27
+    z = (z * 0x94D049BB133111EB) & M
+    z ^= z >> 31
+    return z
+
+
+def test_generator_host_twin_against_python():
+    M = (1 << 64) - 1
+    seed, stream, replica, step = synth.SEED, 1, 5, 499
+    k = _mix64((seed + 0x9E3779B97F4A7C15) & M)
+    for x in (stream, replica, step):
+        k = _mix64((k + x) & M)
+    assert synth.key(stream, replica, step) == k
+    c = np.float32(1e-3 / synth.IRWIN_HALL_SD)
+    idx = np.array([0, 1, 2, 1000, 234119167, (1 << 33) + 5], dtype=np.uint64)
+    got = synth.host_gather_f32(idx, k, 1e-3)
+    got16 = synth.host_gather_f16(idx, k)
+    for j, i in enumerate(idx.tolist()):
+        u = _mix64((k + i * 0x9E3779B97F4A7C15) & M)
+        s = sum((u >> sh) & 0xFFFF for sh in (0, 16, 32, 48)) - 131070
+        assert got[j] == np.float32(s) * c
+        assert np.array([got16[j]], dtype=np.uint16).view(np.float16)[0] == (s >> 6) / 8.0
+    x = synth.host_fill_f32(1 << 20, k, 1e-3)
+    assert abs(float(x.std()) - 1e-3) < 2e-5 and abs(float(x.mean())) < 5e-6
+    assert np.array_equal(synth.host_fill_f32(1000, k, 1e-3, first=77), synth.host_gather_f32(
+        np.arange(77, 1077, dtype=np.uint64), k, 1e-3))
