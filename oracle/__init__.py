@@ -148,11 +148,12 @@ def nesterov_step(theta0, b, grad, lr, mu):
     fn(_p(theta0, dt), _p(b, dt), _p(grad, dt), theta0.size, lr, mu)
 
 
-def outer_step(theta0, b, theta, outer_lr, mu, pg_f16):
-    """Whole outer step, float32, in place.  theta is [k][n]."""
+def outer_step(theta0, b, theta, outer_lr, mu, pg_f16, scratch=None):
+    """Whole outer step, float32, in place.  theta is [k][n].  scratch: optional preallocated
+    (delta[k][n], mean[n]) work arrays."""
     k, n = theta.shape
-    d = np.empty((k, n), dtype=np.float32)
-    mean = np.empty(n, dtype=np.float32)
+    d, mean = scratch if scratch is not None else (np.empty((k, n), dtype=np.float32),
+                                                   np.empty(n, dtype=np.float32))
     lib().oracle_outer_step_f32(_p(theta0, np.float32), _p(b, np.float32), _p(theta, np.float32),
                                 k, n, outer_lr, mu, 1 if pg_f16 else 0, _p(d, np.float32),
                                 _p(mean, np.float32))

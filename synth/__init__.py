@@ -92,6 +92,8 @@ def device():
         L.synth_device_fill_f32.restype = i
         L.synth_device_fill_f16.argtypes = [vp, vp, u64, sz, u64, u64, u32, vp]
         L.synth_device_fill_f16.restype = i
+        L.synth_device_copy.argtypes = [vp, vp, sz, vp]
+        L.synth_device_copy.restype = i
         _device = L
     return _device
 
@@ -216,3 +218,10 @@ def device_fill_f16(ptr, n, k, kind_ptr=None, first=0, inject_key=0, inject_peri
                                         stream)
     if rc != 0:
         raise RuntimeError("synth_device_fill_f16: hip error %d" % rc)
+
+
+def device_copy(dst_ptr, src_ptr, n_bytes, stream=None):
+    """Plain device-to-device copy kernel of known size (reference for counter calibration)."""
+    rc = device().synth_device_copy(dst_ptr, src_ptr, n_bytes, stream)
+    if rc != 0:
+        raise RuntimeError("synth_device_copy: hip error %d" % rc)

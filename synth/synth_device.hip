@@ -38,6 +38,13 @@ __global__ void fill_f16_kernel(uint16_t* __restrict__ out, const uint8_t* __res
   }
 }
 
+// Plain copy of n 16-byte vectors: the known-size reference that hardware-counter readings of
+// HBM traffic are scaled by.
+__global__ void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
 unsigned grid_for(size_t n) {
   size_t blocks = (n + 255) / 256;
   if (blocks > 65536) blocks = 65536;
@@ -64,6 +71,15 @@ int synth_device_fill_f16(void* out, const void* kind, uint64_t first, size_t n,
   hipLaunchKernelGGL(fill_f16_kernel, dim3(grid_for(n)), dim3(256), 0, (hipStream_t)stream,
                      (uint16_t*)out, (const uint8_t*)kind, first, n, key, inject_key,
                      inject_period);
+  return (int)hipGetLastError();
+}
+
+// Copies n_bytes (a multiple of 16) from src to dst, one 16-byte vector per thread.
+int synth_device_copy(void* dst, const void* src, size_t n_bytes, void* stream) {
+  const size_t n = n_bytes / 16;
+  if (n == 0) return 0;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     (hipStream_t)stream, (const uint4*)src, (uint4*)dst, n);
   return (int)hipGetLastError();
 }
 
