@@ -224,6 +224,8 @@ int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco
   e = hipGetDeviceProperties(&prop, c->device);
   if (e != hipSuccess) return bail(fail_hip(c, "hipGetDeviceProperties", e));
   c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  if (prop.maxSharedMemoryPerMultiProcessor >= 64 * 1024)
+    c->tune.lds_per_cu = (uint32_t)prop.maxSharedMemoryPerMultiProcessor;
 
   rc = check_device_range(c, cfg->arena, c->lay.arena_bytes, "arena");
   if (rc != DILOCO_OK) return bail(rc);
@@ -412,6 +414,8 @@ int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value) {
   else if (n == "outer_vec" && (value == 1 || value == 2)) t.outer_vec = value;
   else if (n == "inner_block" && (value == 64 || value == 128 || value == 256)) t.inner_block = value;
   else if (n == "outer_block" && (value == 64 || value == 256)) t.outer_block = value;
+  else if (n == "inner_waves" && value >= 0 && value <= 32) t.inner_waves = value;
+  else if (n == "outer_waves" && value >= 0 && value <= 32) t.outer_waves = value;
   else if (n == "inner_nt" && (value == 0 || value == 1)) t.inner_nt = value;
   else if (n == "outer_nt" && (value == 0 || value == 1)) t.outer_nt = value;
   else if (n == "check_persist" && value >= 0 && value <= 64) t.check_persist = value;

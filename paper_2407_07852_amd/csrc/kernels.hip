@@ -35,6 +35,12 @@ __device__ __forceinline__ void st(T* p, T x) {
   else *p = x;
 }
 
+// The mixed read/write streaming kernels run fastest with a LIMITED number of waves resident per
+// CU (about 10 MB of loads in flight chip-wide; more in-flight requests lower the sustained HBM
+// bandwidth).  Residency is capped by giving every workgroup a slice of the CU's LDS as dynamic
+// shared memory that the kernel never touches.
+extern __shared__ float occupancy_pad[];
+
 // Tile handled by this workgroup (one tile per workgroup: many small workgroups in dispatch
 // order keep every stream's in-flight addresses in a tight window, which measured faster than
 // any grid-stride variant).  With xcd_remap the hardware's round-robin of consecutive
@@ -68,6 +74,7 @@ __global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32
   const uint32_t r = blockIdx.y;
   const uint32_t tile = tile_of_block(xcd_remap);
   if (tile >= tiles) return;
+  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // keeps the LDS pad allocated
 
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta + (size_t)r * a.stride);
   f32x4* __restrict__ m_p = reinterpret_cast<f32x4*>(a.m + (size_t)r * a.stride);
@@ -155,6 +162,7 @@ __global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint3
                                                         int xcd_remap) {
   const uint32_t tile = tile_of_block(xcd_remap);
   if (tile >= tiles) return;
+  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // keeps the LDS pad allocated
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
@@ -314,6 +322,18 @@ __global__ __launch_bounds__(kBlock) void cast_f16_kernel(const float* __restric
   }
 }
 
+// Dynamic LDS bytes per workgroup so that at most `waves_per_cu` waves of B-thread workgroups
+// are resident on a CU with `lds_per_cu` bytes of LDS (0 = no cap).
+uint32_t pad_lds_bytes(int waves_per_cu, int block, uint32_t lds_per_cu) {
+  if (waves_per_cu <= 0) return 0;
+  int groups = waves_per_cu / (block / 64);
+  if (groups < 1) groups = 1;
+  if (groups >= 32) return 0;
+  uint32_t bytes = (lds_per_cu / (uint32_t)groups) & ~511u;
+  if (bytes > 65536u) bytes = 65536u;  // default per-workgroup limit; caps at 2 groups per CU
+  return bytes;
+}
+
 // Grid size in x for `tiles` tiles: one block per tile, or persist*n_cu grid-stride blocks.
 uint32_t grid_x(uint64_t tiles, int persist, int n_cu, bool xcd_remap) {
   uint64_t g = tiles;
@@ -336,8 +356,9 @@ static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int
                                  hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
   const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0), (uint32_t)k);
-  hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT>), grid, dim3(B), 0, s, a,
-                     (uint32_t)tiles, t.xcd_remap);
+  hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT>), grid, dim3(B),
+                     pad_lds_bytes(t.inner_waves, B, t.lds_per_cu), s, a, (uint32_t)tiles,
+                     t.xcd_remap);
   return hipGetLastError();
 }
 
@@ -373,8 +394,9 @@ template <int B, int K, int V, bool F16, bool NT>
 static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
   const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0));
-  hipLaunchKernelGGL((outer_fused_kernel<B, K, V, F16, NT>), grid, dim3(B), 0, s, a,
-                     (uint32_t)tiles, t.xcd_remap);
+  hipLaunchKernelGGL((outer_fused_kernel<B, K, V, F16, NT>), grid, dim3(B),
+                     pad_lds_bytes(t.outer_waves, B, t.lds_per_cu), s, a, (uint32_t)tiles,
+                     t.xcd_remap);
   return hipGetLastError();
 }
 
