@@ -108,6 +108,50 @@ def run_workload(name, k, H, pg_f16, rounds, warmup, torch, D, synth):
     }
 
 
+def run_mixed_precision(k, reps, torch, D, synth):
+    """Rows a1 + a2 in mixed precision: binary16 gradients scaled by 65536 on the 150M set plus
+    2000 ragged tensors; the inf/NaN check, then the inner step with the unscale fused in."""
+    wl = synth.WORKLOADS["stress"]()
+    n = wl.n_params
+    stream = torch.cuda.current_stream()
+    dl = D.DiLoCo(wl.numel, k, fill_theta0=lambda t, lay, off: t.normal_(0, 0.02))
+    kind = torch.from_numpy(wl.kind_map(dl.offsets, dl.layout.n_pad)).cuda()
+    dl.theta0.mul_(kind != 0)
+    D.diloco_destroy(dl.ctx)                      # re-initialise with clean pads
+    dl.ctx = D.diloco_init(dl.cfg)
+    g = dl.new_grads(torch.float16)
+    for r in range(k):
+        synth.device_fill_f16(g[r].data_ptr(), dl.layout.n_pad, synth.key(synth.STREAM_GRADS, r, 0),
+                              kind.data_ptr(), stream=stream.cuda_stream)
+    flags = dl.new_flags()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps + 1)]
+    dl.unscale_check(g, 1.0 / 65536, flags)
+    dl.inner_step(g, flags=flags)
+    torch.cuda.synchronize()
+    ev[0].record(stream)
+    for i in range(reps):
+        dl.unscale_check(g, 1.0 / 65536, flags)
+        ev[2 * i + 1].record(stream)
+        dl.inner_step(g, flags=flags)
+        ev[2 * i + 2].record(stream)
+    torch.cuda.synchronize()
+    chk = sum(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(reps)) / reps
+    inn = sum(ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(reps)) / reps
+    assert flags.cpu().tolist() == [0] * k and dl.steps() == [reps + 1] * k
+    dl.close()
+    del dl, g, kind
+    torch.cuda.empty_cache()
+    cb, ib = 2 * n * k, inner_bytes(n, k, g16=True)
+    return {"config": {"workload": "llama150m + 2000 ragged tensors x %d workers, FP16 gradients "
+                                   "scaled by 65536" % k, "n_params": n, "n_tensors": len(wl.shapes)},
+            "unscale_check": {"ms": chk, "bytes": cb, "GBps": cb / chk / 1e6,
+                              "frac_of_peak": cb / chk / 1e6 / HBM_PEAK_GBS,
+                              "note": "includes the flag-clearing launch"},
+            "inner_step_fp16_grads": {"ms": inn, "bytes": ib, "GBps": ib / inn / 1e6,
+                                      "frac_of_peak": ib / inn / 1e6 / HBM_PEAK_GBS},
+            "launches_timed": reps}
+
+
 def cpu_baseline(k, log2_slice=25, inner_reps=100, outer_reps=100):
     """The oracle as it stands, timed on this host's cores on a bounded sample of the workload:
     a contiguous slice of the flat buffers, k workers; its inner-step and outer-step loops are
@@ -253,6 +297,8 @@ def main():
                        "inner_step": also["inner"], "outer_step": also["outer"],
                        "roofline": roof(also, "inner"), "roofline_outer": roof(also, "outer"),
                        "finite": also["finite"], "note": also["warmup_note"]}
+    if not args.no_also and args.workload == "llama150m":
+        out["mixed_precision"] = run_mixed_precision(4, 20, torch, D, synth)
     if not args.no_cpu:
         cb = cpu_baseline(args.k)
         n = main_res["n_params"]

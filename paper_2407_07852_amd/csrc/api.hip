@@ -3,7 +3,6 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -108,11 +107,9 @@ void plan(const diloco_config* cfg, diloco_layout* lay, uint64_t* offsets) {
   const uint64_t k = cfg->k_workers;
   lay->n_pad = n_pad;
   // All flat buffers start 2 MiB-aligned relative to each other: the k+2 streams of a tile then
-  // share their offset inside the GPU's 2 MiB page fragments (measured +4 % on the outer step).
-  uint64_t align_elems = DILOCO_STRIDE_ALIGN_BYTES / 4;
-  if (const char* e = getenv("DILOCO_STRIDE_ALIGN")) align_elems = strtoull(e, nullptr, 10) / 4;
-  if (align_elems == 0) align_elems = 1;
-  lay->stride = round_up(n_pad, align_elems);
+  // share their offset inside the GPU's 2 MiB page fragments (measured +4 % on the outer step; larger alignments and skews
+  // between the buffers measured neutral or worse).
+  lay->stride = round_up(n_pad, DILOCO_STRIDE_ALIGN_BYTES / 4);
   lay->off_theta0 = 0;
   lay->off_mom = lay->stride * 4;
   lay->off_theta = 2 * lay->stride * 4;
@@ -414,10 +411,13 @@ int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value) {
   else if (n == "outer_vec" && (value == 1 || value == 2)) t.outer_vec = value;
   else if (n == "inner_block" && (value == 64 || value == 128 || value == 256)) t.inner_block = value;
   else if (n == "outer_block" && (value == 64 || value == 256)) t.outer_block = value;
-  else if (n == "inner_waves" && value >= 0 && value <= 32) t.inner_waves = value;
-  else if (n == "outer_waves" && value >= 0 && value <= 32) t.outer_waves = value;
+  else if (n == "inner_waves" && value >= -1 && value <= 32) t.inner_waves = value;
+  else if (n == "outer_waves" && value >= -1 && value <= 32) t.outer_waves = value;
   else if (n == "inner_nt" && (value == 0 || value == 1)) t.inner_nt = value;
   else if (n == "outer_nt" && (value == 0 || value == 1)) t.outer_nt = value;
+  else if (n == "check_block" && (value == 64 || value == 256)) t.check_block = value;
+  else if (n == "check_vec" && (value == 1 || value == 2 || value == 4 || value == 8)) t.check_vec = value;
+  else if (n == "check_waves" && value >= 0 && value <= 32) t.check_waves = value;
   else if (n == "check_persist" && value >= 0 && value <= 64) t.check_persist = value;
   else if (n == "xcd_remap" && (value == 0 || value == 1)) t.xcd_remap = value;
   else return fail(ctx, DILOCO_ERR_INVALID_ARG, "unknown tuning knob or value: %s=%d", name, value);

@@ -19,13 +19,15 @@ struct Tuning {
   int inner_block = 64;   // threads per workgroup (64, 128, 256)
   int inner_vec = 1;      // 128-bit vectors per thread per stream (1, 2, 4)
   int inner_nt = 1;       // nontemporal loads/stores
-  int inner_waves = 12;   // resident waves per CU (0 = hardware maximum)
+  int inner_waves = -1;   // resident waves per CU: -1 = auto, 0 = hardware maximum
   int outer_block = 64;   // 64 or 256
   int outer_vec = 1;      // 1 or 2
   int outer_nt = 1;
-  int outer_waves = 4;
-  int check_vec = 4;
-  int check_persist = 8;  // inf/NaN check: grid-stride blocks per CU (0: one tile per block)
+  int outer_waves = -1;
+  int check_block = 256;  // 64 or 256
+  int check_vec = 4;      // 1, 2, 4 (8 with 64-thread blocks)
+  int check_waves = 16;   // resident waves per CU (0 = hardware maximum)
+  int check_persist = 0;  // inf/NaN check: grid-stride blocks per CU (0: one tile per block)
   uint32_t lds_per_cu = 160 * 1024;  // set from the device properties at init
   int xcd_remap = 0;      // 1: give each of the 8 XCDs a contiguous range of tiles
 };

@@ -201,41 +201,42 @@ __global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint3
   }
 }
 
-// Any k (run-time loop over the workers); one vector per thread.
+// Any k (run-time loop over the workers): one single-wave workgroup per 256-element tile.
 template <bool F16, bool NT>
-__global__ __launch_bounds__(kBlock) void outer_fused_anyk_kernel(const OuterArgs a,
-                                                                  uint32_t tiles) {
+__global__ __launch_bounds__(64) void outer_fused_anyk_kernel(const OuterArgs a, uint32_t tiles) {
+  const uint32_t tile = blockIdx.x;
+  if (tile >= tiles) return;
+  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // keeps the LDS pad allocated
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
   const size_t rstride = a.stride / kVecElems;
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    const size_t i = (size_t)tile * kBlock + threadIdx.x;
-    f32x4 t0 = ld<NT>(t0_p + i);
-    f32x4 b = ld<NT>(b_p + i);
-    f32x4 s;
-    {
-      const f32x4 th = ld<NT>(th_p + i);
+  const size_t i = (size_t)tile * 64 + threadIdx.x;
+  f32x4 t0 = ld<NT>(t0_p + i);
+  f32x4 b = ld<NT>(b_p + i);
+  f32x4 s;
+  {
+    const f32x4 th = ld<NT>(th_p + i);
 #pragma unroll
-      for (int c = 0; c < kVecElems; ++c) s[c] = pseudo_grad<F16>(t0[c], th[c]);
-    }
-    for (int r = 1; r < a.k; ++r) {
-      const f32x4 th = ld<NT>(th_p + (size_t)r * rstride + i);
-#pragma unroll
-      for (int c = 0; c < kVecElems; ++c) s[c] = s[c] + pseudo_grad<F16>(t0[c], th[c]);
-    }
-#pragma unroll
-    for (int c = 0; c < kVecElems; ++c) {
-      const float dbar = s[c] / a.kf;
-      float t = t0[c], bb = b[c];
-      nesterov_elem(t, bb, dbar, a.lr, a.mu);
-      t0[c] = t;
-      b[c] = bb;
-    }
-    st<NT>(t0_p + i, t0);
-    st<NT>(b_p + i, b);
-    for (int r = 0; r < a.k; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0);
+    for (int c = 0; c < kVecElems; ++c) s[c] = pseudo_grad<F16>(t0[c], th[c]);
   }
+#pragma unroll 4
+  for (int r = 1; r < a.k; ++r) {
+    const f32x4 th = ld<NT>(th_p + (size_t)r * rstride + i);
+#pragma unroll
+    for (int c = 0; c < kVecElems; ++c) s[c] = s[c] + pseudo_grad<F16>(t0[c], th[c]);
+  }
+#pragma unroll
+  for (int c = 0; c < kVecElems; ++c) {
+    const float dbar = s[c] / a.kf;
+    float t = t0[c], bb = b[c];
+    nesterov_elem(t, bb, dbar, a.lr, a.mu);
+    t0[c] = t;
+    b[c] = bb;
+  }
+  st<NT>(t0_p + i, t0);
+  st<NT>(b_p + i, b);
+  for (int r = 0; r < a.k; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -251,36 +252,42 @@ __device__ __forceinline__ bool nonfinite_f32(uint32_t w) {
   return (w & 0x7f800000u) == 0x7f800000u;
 }
 
-template <int V, bool G16>
-__global__ __launch_bounds__(kBlock) void unscale_check_kernel(const void* g, uint64_t g_stride,
-                                                               uint32_t tiles,
-                                                               int32_t* found_inf) {
+template <int B, int V, bool G16>
+__global__ __launch_bounds__(B) void unscale_check_kernel(const void* g, uint64_t g_stride,
+                                                          uint32_t tiles, int32_t* found_inf) {
+  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // keeps the LDS pad allocated
   const uint32_t r = blockIdx.y;
   const size_t elem_bytes = G16 ? 2 : 4;
   const u32x4* __restrict__ p = reinterpret_cast<const u32x4*>(
       static_cast<const char*>(g) + (size_t)r * g_stride * elem_bytes);
-  constexpr uint32_t kTileVecs = kBlock * V;
+  constexpr uint32_t kTileVecs = B * V;
   bool bad = false;
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const size_t base = (size_t)tile * kTileVecs + threadIdx.x;
     u32x4 w[V];
 #pragma unroll
-    for (int j = 0; j < V; ++j) w[j] = ld<true>(p + base + (size_t)j * kBlock);
+    for (int j = 0; j < V; ++j) w[j] = ld<true>(p + base + (size_t)j * B);
 #pragma unroll
     for (int j = 0; j < V; ++j) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) bad |= G16 ? nonfinite_f16x2(w[j][c]) : nonfinite_f32(w[j][c]);
     }
   }
-  __shared__ int wave_bad[kBlock / 64];
+  // Cross-lane any-reduce: ballot inside each wave, LDS across the block's waves, then one
+  // atomic per block and only when something was found (so clean gradients cost no atomics).
   const bool wave_any = __ballot(bad) != 0ull;
-  if ((threadIdx.x & 63) == 0) wave_bad[threadIdx.x >> 6] = wave_any ? 1 : 0;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int any = 0;
+  if constexpr (B == 64) {
+    if (threadIdx.x == 0 && wave_any) atomicOr(found_inf + r, 1);
+  } else {
+    __shared__ int wave_bad[B / 64];
+    if ((threadIdx.x & 63) == 0) wave_bad[threadIdx.x >> 6] = wave_any ? 1 : 0;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int any = 0;
 #pragma unroll
-    for (int w = 0; w < kBlock / 64; ++w) any |= wave_bad[w];
-    if (any) atomicOr(found_inf + r, 1);
+      for (int w = 0; w < B / 64; ++w) any |= wave_bad[w];
+      if (any) atomicOr(found_inf + r, 1);
+    }
   }
 }
 
@@ -324,6 +331,13 @@ __global__ __launch_bounds__(kBlock) void cast_f16_kernel(const float* __restric
 
 // Dynamic LDS bytes per workgroup so that at most `waves_per_cu` waves of B-thread workgroups
 // are resident on a CU with `lds_per_cu` bytes of LDS (0 = no cap).
+// Automatic residency: about 44 KiB of loads in flight per CU (measured optimum on MI355X for
+// both steps: 11 waves x 4 KiB for the inner step, 4 waves x 10 KiB for the outer step at k=8).
+int auto_waves(int load_bytes_per_wave) {
+  int w = (44 * 1024 + load_bytes_per_wave / 2) / load_bytes_per_wave;
+  return w < 2 ? 2 : (w > 16 ? 16 : w);
+}
+
 uint32_t pad_lds_bytes(int waves_per_cu, int block, uint32_t lds_per_cu) {
   if (waves_per_cu <= 0) return 0;
   int groups = waves_per_cu / (block / 64);
@@ -357,7 +371,9 @@ static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
   const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0), (uint32_t)k);
   hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT>), grid, dim3(B),
-                     pad_lds_bytes(t.inner_waves, B, t.lds_per_cu), s, a, (uint32_t)tiles,
+                     pad_lds_bytes(t.inner_waves < 0 ? auto_waves((G16 ? 3584 : 4096) * V) : t.inner_waves, B,
+                                   t.lds_per_cu),
+                     s, a, (uint32_t)tiles,
                      t.xcd_remap);
   return hipGetLastError();
 }
@@ -395,7 +411,9 @@ static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, int n_cu, 
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
   const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0));
   hipLaunchKernelGGL((outer_fused_kernel<B, K, V, F16, NT>), grid, dim3(B),
-                     pad_lds_bytes(t.outer_waves, B, t.lds_per_cu), s, a, (uint32_t)tiles,
+                     pad_lds_bytes(t.outer_waves < 0 ? auto_waves((K + 2) * 1024 * V) : t.outer_waves, B,
+                                   t.lds_per_cu),
+                     s, a, (uint32_t)tiles,
                      t.xcd_remap);
   return hipGetLastError();
 }
@@ -421,10 +439,10 @@ static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, int n_cu, 
     case 7: return launch_outer_v<7, F16, NT>(a, t, n_cu, s);
     case 8: return launch_outer_v<8, F16, NT>(a, t, n_cu, s);
     default: {
-      const uint64_t tiles = a.n_pad / (uint64_t)(kBlock * kVecElems);
-      const dim3 grid(grid_x(tiles, 16, n_cu, false));
-      hipLaunchKernelGGL((outer_fused_anyk_kernel<F16, NT>), grid, dim3(kBlock), 0, s, a,
-                         (uint32_t)tiles);
+      const uint64_t tiles = a.n_pad / (uint64_t)(64 * kVecElems);
+      const int waves = t.outer_waves < 0 ? auto_waves((a.k + 2) * 1024) : t.outer_waves;
+      hipLaunchKernelGGL((outer_fused_anyk_kernel<F16, NT>), dim3((uint32_t)tiles), dim3(64),
+                         pad_lds_bytes(waves, 64, t.lds_per_cu), s, a, (uint32_t)tiles);
       return hipGetLastError();
     }
   }
@@ -437,22 +455,38 @@ hipError_t launch_outer(const OuterArgs& a, const Tuning& t, int n_cu, hipStream
                     : launch_outer_k<false, false>(a, t, n_cu, s);
 }
 
+template <int B, int V>
+static hipError_t launch_check_t(const void* g, uint64_t g_stride, uint64_t n_pad, int k, bool g16,
+                                 int32_t* found_inf, const Tuning& t, int n_cu, hipStream_t s) {
+  const uint64_t vec_elems = g16 ? 8 : 4;
+  const uint64_t tiles = n_pad / (vec_elems * B * V);
+  const dim3 grid(grid_x(tiles, t.check_persist, n_cu, false), (uint32_t)k);
+  const uint32_t lds = pad_lds_bytes(t.check_waves, B, t.lds_per_cu);
+  if (g16)
+    hipLaunchKernelGGL((unscale_check_kernel<B, V, true>), grid, dim3(B), lds, s, g, g_stride,
+                       (uint32_t)tiles, found_inf);
+  else
+    hipLaunchKernelGGL((unscale_check_kernel<B, V, false>), grid, dim3(B), lds, s, g, g_stride,
+                       (uint32_t)tiles, found_inf);
+  return hipGetLastError();
+}
+
 hipError_t launch_check(const void* g, uint64_t g_stride, uint64_t n_pad, int k, bool g16,
                         int32_t* found_inf, const Tuning& t, int n_cu, hipStream_t s) {
   hipLaunchKernelGGL(zero_flags_kernel, dim3(1), dim3(64), 0, s, found_inf, k);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  constexpr int V = 4;
-  const uint64_t vec_elems = g16 ? 8 : 4;
-  const uint64_t tiles = n_pad / (vec_elems * kBlock * V);
-  const dim3 grid(grid_x(tiles, t.check_persist, n_cu, false), (uint32_t)k);
-  if (g16)
-    hipLaunchKernelGGL((unscale_check_kernel<V, true>), grid, dim3(kBlock), 0, s, g, g_stride,
-                       (uint32_t)tiles, found_inf);
-  else
-    hipLaunchKernelGGL((unscale_check_kernel<V, false>), grid, dim3(kBlock), 0, s, g, g_stride,
-                       (uint32_t)tiles, found_inf);
-  return hipGetLastError();
+  const bool small = t.check_block == 64;
+  switch (t.check_vec) {
+    case 1: return small ? launch_check_t<64, 1>(g, g_stride, n_pad, k, g16, found_inf, t, n_cu, s)
+                         : launch_check_t<256, 1>(g, g_stride, n_pad, k, g16, found_inf, t, n_cu, s);
+    case 2: return small ? launch_check_t<64, 2>(g, g_stride, n_pad, k, g16, found_inf, t, n_cu, s)
+                         : launch_check_t<256, 2>(g, g_stride, n_pad, k, g16, found_inf, t, n_cu, s);
+    case 8: return small ? launch_check_t<64, 8>(g, g_stride, n_pad, k, g16, found_inf, t, n_cu, s)
+                         : launch_check_t<256, 4>(g, g_stride, n_pad, k, g16, found_inf, t, n_cu, s);
+    default: return small ? launch_check_t<64, 4>(g, g_stride, n_pad, k, g16, found_inf, t, n_cu, s)
+                          : launch_check_t<256, 4>(g, g_stride, n_pad, k, g16, found_inf, t, n_cu, s);
+  }
 }
 
 hipError_t launch_init_state(float* theta0, float* mom, float* theta, float* m, float* v,

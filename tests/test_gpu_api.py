@@ -42,13 +42,20 @@ def test_round_for_various_k(k, pg_f16):
 
 @pytest.mark.parametrize("tune", [dict(inner_block=256, inner_vec=4, outer_block=256, outer_vec=2),
                                   dict(inner_block=128, inner_vec=2, xcd_remap=1),
-                                  dict(inner_nt=0, outer_nt=0)])
+                                  dict(inner_nt=0, outer_nt=0),
+                                  dict(inner_waves=0, outer_waves=0, check_waves=0),
+                                  dict(inner_waves=3, outer_waves=16, check_block=64, check_vec=8,
+                                       check_persist=2)])
 def test_launch_shapes_do_not_change_results(tune):
     wl = synth.tiny()
     gpu, cpu = GpuSide(wl, 4, True), CpuSide(wl, 4, True)
     gpu.dl.set_tuning(**tune)
+    flags = gpu.dl.new_flags()
     for step in range(2):
-        gpu.dl.inner_step(gpu.gen_grads(step))
+        g = gpu.gen_grads(step)
+        gpu.dl.unscale_check(g, 1.0, flags)
+        assert flags.cpu().tolist() == [0] * 4
+        gpu.dl.inner_step(g, flags=flags)
         cpu.o.inner_step(cpu.gen_grads(step))
     gpu.dl.outer_step()
     cpu.o.outer_step()
