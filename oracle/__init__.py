@@ -27,6 +27,11 @@ def lib():
             "oracle_cast_f16_to_f32": (None, [vp, vp, sz]),
             "oracle_adamw_step_f32": (None, [vp, vp, vp, vp, sz, f64, f64, f64, f64, f64, vp, vp]),
             "oracle_adamw_step_f64": (None, [vp, vp, vp, vp, sz, f64, f64, f64, f64, f64, vp, vp]),
+            "oracle_adamw_step_groups_f32": (None, [vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, f64, f64,
+                                                    f64, f64, vp, vp]),
+            "oracle_adamw_step_groups_f64": (None, [vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, f64, f64,
+                                                    f64, f64, vp, vp]),
+            "oracle_lr_at": (f64, [u64, u64, u64, f64, f64]),
             "oracle_unscale_f16": (None, [vp, f32, vp, sz]),
             "oracle_found_inf_f16": (i32, [vp, sz]),
             "oracle_found_inf_f32": (i32, [vp, sz]),
@@ -100,6 +105,39 @@ def adamw_step(st, g, lr, beta1, beta2, eps, weight_decay):
     fn(_p(st.theta, st.dtype), _p(st.m, st.dtype), _p(st.v, st.dtype), _p(g, st.dtype),
        st.theta.size, lr, beta1, beta2, eps, weight_decay, C.addressof(st.p1), C.addressof(st.p2))
     st.t += 1
+
+
+class ParamGroups:
+    """Per-tensor parameter groups over a flat layout: tensor t occupies
+    [offsets[t], offsets[t]+numel[t]) and belongs to group group_of_tensor[t]."""
+
+    def __init__(self, offsets, numel, group_of_tensor, lr_scale, weight_decay):
+        self.offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+        self.numel = np.ascontiguousarray(numel, dtype=np.uint64)
+        self.group_of_tensor = np.ascontiguousarray(group_of_tensor, dtype=np.uint8)
+        self.lr_scale = np.ascontiguousarray(lr_scale, dtype=np.float64)
+        self.weight_decay = np.ascontiguousarray(weight_decay, dtype=np.float64)
+        assert self.offsets.size == self.numel.size == self.group_of_tensor.size
+        assert self.lr_scale.size == self.weight_decay.size > int(self.group_of_tensor.max())
+
+
+def adamw_step_groups(st, g, groups, lr, beta1, beta2, eps):
+    """One AdamW step of one worker with per-tensor parameter groups, in place on st."""
+    g = np.ascontiguousarray(g, dtype=st.dtype).reshape(-1)
+    assert g.size == st.theta.size
+    fn = (lib().oracle_adamw_step_groups_f32 if st.dtype == np.float32
+          else lib().oracle_adamw_step_groups_f64)
+    G = groups
+    fn(_p(st.theta, st.dtype), _p(st.m, st.dtype), _p(st.v, st.dtype), _p(g, st.dtype),
+       G.numel.size, _p(G.offsets, np.uint64), _p(G.numel, np.uint64),
+       _p(G.group_of_tensor, np.uint8), _p(G.lr_scale, np.float64),
+       _p(G.weight_decay, np.float64), lr, beta1, beta2, eps,
+       C.addressof(st.p1), C.addressof(st.p2))
+    st.t += 1
+
+
+def lr_at(step, warmup_steps, total_steps, base_lr, final_ratio=1.0):
+    return float(lib().oracle_lr_at(step, warmup_steps, total_steps, base_lr, final_ratio))
 
 
 def unscale_f16(g16_bits, inv_scale):
@@ -188,6 +226,7 @@ class DiLoCoOracle:
         self.theta0 = theta_init.copy()
         self.b = np.zeros_like(self.theta0)
         self.workers = [AdamWState(theta_init) for _ in range(k)]
+        self.groups = None   # optional ParamGroups
 
     def inner_step(self, grads, found_inf_flags=None, lr=None, inv_scale=None):
         """grads[r]: float32 array, or uint16 binary16 codes together with inv_scale."""
@@ -198,7 +237,10 @@ class DiLoCoOracle:
             g = grads[r]
             if g.dtype == np.uint16:
                 g = unscale_f16(g, inv_scale)
-            adamw_step(st, g, lr0 if lr is None else lr, b1, b2, eps, wd)
+            if self.groups is not None:
+                adamw_step_groups(st, g, self.groups, lr0 if lr is None else lr, b1, b2, eps)
+            else:
+                adamw_step(st, g, lr0 if lr is None else lr, b1, b2, eps, wd)
 
     def outer_step(self):
         theta = np.stack([st.theta for st in self.workers])

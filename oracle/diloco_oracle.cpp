@@ -97,9 +97,11 @@ float f16_to_f32(uint16_t h) {
 // p1, p2 are the worker's running products beta1^t, beta2^t (double, start 1);
 // the step advances them, i.e. the worker's step count t grows by one.
 // ---------------------------------------------------------------------------
+// The element loop of one AdamW step over [first, first+n) with the scalars of one parameter
+// group.  bc1 = 1 - beta1^t, bc2 = 1 - beta2^t.
 template <class T>
-void adamw_step(T* theta, T* m, T* v, const T* g, size_t n, double lr, double beta1, double beta2,
-                double eps, double weight_decay, double* p1, double* p2) {
+void adamw_elements(T* theta, T* m, T* v, const T* g, size_t first, size_t n, double lr,
+                    double beta1, double beta2, double eps, double weight_decay, T bc1, T bc2) {
   // Hyper-parameters are doubles; each scalar the loop uses is formed in double and
   // rounded to the working type once.
   const T b1 = (T)beta1, b2 = (T)beta2;
@@ -107,12 +109,8 @@ void adamw_step(T* theta, T* m, T* v, const T* g, size_t n, double lr, double be
   const T one_minus_b2 = (T)(1.0 - beta2);
   const T lr_t = (T)lr, eps_t = (T)eps;
   const T lr_wd = (T)(lr * weight_decay);
-  *p1 *= beta1;
-  *p2 *= beta2;
-  const T bc1 = (T)(1.0 - *p1);   // 1 - beta1^t
-  const T bc2 = (T)(1.0 - *p2);   // 1 - beta2^t
 #pragma omp parallel for schedule(static)
-  for (size_t i = 0; i < n; ++i) {
+  for (size_t i = first; i < first + n; ++i) {
     const T gi = g[i];
     const T mi = b1 * m[i] + one_minus_b1 * gi;
     const T vi = b2 * v[i] + one_minus_b2 * (gi * gi);
@@ -122,6 +120,36 @@ void adamw_step(T* theta, T* m, T* v, const T* g, size_t n, double lr, double be
     theta[i] = decayed - lr_t * (m_hat / (std::sqrt(v_hat) + eps_t));
     m[i] = mi;
     v[i] = vi;
+  }
+}
+
+template <class T>
+void adamw_step(T* theta, T* m, T* v, const T* g, size_t n, double lr, double beta1, double beta2,
+                double eps, double weight_decay, double* p1, double* p2) {
+  *p1 *= beta1;
+  *p2 *= beta2;
+  const T bc1 = (T)(1.0 - *p1);   // 1 - beta1^t
+  const T bc2 = (T)(1.0 - *p2);   // 1 - beta2^t
+  adamw_elements<T>(theta, m, v, g, 0, n, lr, beta1, beta2, eps, weight_decay, bc1, bc2);
+}
+
+// Parameter groups: tensor t (elements [offset[t], offset[t]+numel[t]) of the flat arrays)
+// belongs to group group_of_tensor[t] and is stepped with that group's learning rate
+// lr * lr_scale[group] and weight decay weight_decay[group].  One step count per worker.
+template <class T>
+void adamw_step_groups(T* theta, T* m, T* v, const T* g, uint32_t n_tensors,
+                       const uint64_t* offset, const uint64_t* numel,
+                       const uint8_t* group_of_tensor, const double* lr_scale,
+                       const double* weight_decay, double lr, double beta1, double beta2,
+                       double eps, double* p1, double* p2) {
+  *p1 *= beta1;
+  *p2 *= beta2;
+  const T bc1 = (T)(1.0 - *p1);
+  const T bc2 = (T)(1.0 - *p2);
+  for (uint32_t t = 0; t < n_tensors; ++t) {
+    const uint8_t grp = group_of_tensor[t];
+    adamw_elements<T>(theta, m, v, g, offset[t], numel[t], lr * lr_scale[grp], beta1, beta2, eps,
+                      weight_decay[grp], bc1, bc2);
   }
 }
 
@@ -192,6 +220,38 @@ void oracle_adamw_step_f64(double* theta, double* m, double* v, const double* g,
                            double lr, double beta1, double beta2, double eps, double weight_decay,
                            double* p1, double* p2) {
   adamw_step<double>(theta, m, v, g, n, lr, beta1, beta2, eps, weight_decay, p1, p2);
+}
+
+void oracle_adamw_step_groups_f32(float* theta, float* m, float* v, const float* g,
+                                  uint32_t n_tensors, const uint64_t* offset,
+                                  const uint64_t* numel, const uint8_t* group_of_tensor,
+                                  const double* lr_scale, const double* weight_decay, double lr,
+                                  double beta1, double beta2, double eps, double* p1, double* p2) {
+  adamw_step_groups<float>(theta, m, v, g, n_tensors, offset, numel, group_of_tensor, lr_scale,
+                           weight_decay, lr, beta1, beta2, eps, p1, p2);
+}
+
+void oracle_adamw_step_groups_f64(double* theta, double* m, double* v, const double* g,
+                                  uint32_t n_tensors, const uint64_t* offset,
+                                  const uint64_t* numel, const uint8_t* group_of_tensor,
+                                  const double* lr_scale, const double* weight_decay, double lr,
+                                  double beta1, double beta2, double eps, double* p1, double* p2) {
+  adamw_step_groups<double>(theta, m, v, g, n_tensors, offset, numel, group_of_tensor, lr_scale,
+                            weight_decay, lr, beta1, beta2, eps, p1, p2);
+}
+
+// Learning-rate schedule on the host: linear warm-up from 0 over warmup_steps, then (when
+// total_steps > warmup_steps) a half-cosine from base_lr down to base_lr*final_ratio at
+// total_steps, constant afterwards; with total_steps == 0 the rate stays at base_lr.
+double oracle_lr_at(uint64_t step, uint64_t warmup_steps, uint64_t total_steps, double base_lr,
+                    double final_ratio) {
+  if (step < warmup_steps) return base_lr * ((double)step / (double)warmup_steps);
+  if (total_steps <= warmup_steps) return base_lr;
+  if (step >= total_steps) return base_lr * final_ratio;
+  const double progress = (double)(step - warmup_steps) / (double)(total_steps - warmup_steps);
+  const double pi = 3.14159265358979323846;
+  const double cosine = 0.5 * (1.0 + std::cos(pi * progress));
+  return base_lr * (final_ratio + (1.0 - final_ratio) * cosine);
 }
 
 // Mixed precision: gradients arrive as binary16 multiplied by the loss scale;
