@@ -38,7 +38,7 @@ def median(xs):
     return xs[len(xs) // 2]
 
 
-def run_workload(name, k, H, pg_f16, rounds, warmup, torch, D, synth):
+def run_workload(name, k, H, pg_f16, rounds, warmup, torch, D, synth, groups=False):
     wl = synth.WORKLOADS[name]()
     n = wl.n_params
     stream = torch.cuda.current_stream()
@@ -51,6 +51,14 @@ def run_workload(name, k, H, pg_f16, rounds, warmup, torch, D, synth):
 
     dl = D.DiLoCo(wl.numel, k, fill_theta0=fill, h_inner_steps=H,
                   pg_dtype=D.F16 if pg_f16 else D.F32)
+    if groups:
+        # matrices decay 0.1; norm vectors and the embedding / LM head: no decay, and the
+        # embeddings at half the learning rate
+        grp = [1 if v else 0 for v in wl.is_vector]
+        grp[-1] = 2
+        if name == "llama1.1b":
+            grp[-2] = 2
+        dl.set_param_groups(grp, [1.0, 1.0, 0.5], [0.1, 0.0, 0.0])
     grads = dl.new_grads()
     for r in range(k):  # one seeded gradient set ~N(0, 1e-3), resident for the whole run
         synth.device_fill_f32(grads[r].data_ptr(), dl.layout.n_pad,
@@ -299,6 +307,11 @@ def main():
                        "finite": also["finite"], "note": also["warmup_note"]}
     if not args.no_also and args.workload == "llama150m":
         out["mixed_precision"] = run_mixed_precision(4, 20, torch, D, synth)
+        pgr = run_workload("llama150m", args.k, 100, False, 1, 0, torch, D, synth, groups=True)
+        out["param_groups"] = {
+            "config": {"workload": "llama150m x %d workers, 100 inner steps, 3 parameter groups "
+                                   "(norm vectors and embedding exempt from weight decay)" % args.k},
+            "inner_step": pgr["inner"]}
     if not args.no_cpu:
         cb = cpu_baseline(args.k)
         n = main_res["n_params"]

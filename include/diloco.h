@@ -63,6 +63,7 @@ enum { /* diloco_get_buffer selector */
 };
 
 #define DILOCO_MAX_WORKERS 64
+#define DILOCO_MAX_GROUPS 8
 #define DILOCO_TENSOR_ALIGN 64u /* elements: every tensor starts on a 256-byte boundary */
 #define DILOCO_TILE 8192u       /* elements: n_pad is a multiple of this */
 #define DILOCO_STRIDE_ALIGN_BYTES 2097152u /* stride*4 is a multiple of this (2 MiB) */
@@ -129,6 +130,28 @@ int diloco_unscale_check(diloco_ctx* ctx, const void* grads, uint64_t grad_strid
  * step. */
 int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
                       int32_t grad_dtype, double lr, const int32_t* found_inf);
+
+/* Per-tensor parameter groups for the inner optimizer: the paper prints one weight decay (0.1)
+ * and one learning rate with 1000 warm-up steps (Appendix A, Table 3); training codes built on
+ * the paper's framework commonly exempt norm and embedding tensors from decay, which is what
+ * groups are for.  group_of_tensor: host array [n_tensors], values < n_groups;
+ * lr_scale, weight_decay: host arrays [n_groups] (finite, >= 0).  From the next inner step on,
+ * every element of a tensor of group g is stepped with learning rate lr*lr_scale[g] and weight
+ * decay weight_decay[g]; cfg->weight_decay is then unused.  n_groups = 0 (pointers ignored)
+ * restores the single group of the config.  1 <= n_groups <= DILOCO_MAX_GROUPS otherwise.
+ * Allocates n_pad/64 bytes of device memory (one group id per 64-element chunk), freed at
+ * destroy; synchronises the stream. */
+int diloco_set_param_groups(diloco_ctx* ctx, const uint8_t* group_of_tensor, uint32_t n_groups,
+                            const double* lr_scale, const double* weight_decay);
+
+/* Learning-rate schedule, host arithmetic only (the result is what a caller passes as `lr` to
+ * diloco_inner_step): linear warm-up from 0 over warmup_steps ("Number of warmup steps 1,000",
+ * Table 3); then, when total_steps > warmup_steps, a half-cosine from base_lr down to
+ * base_lr*final_ratio reached at total_steps and held afterwards; total_steps = 0 keeps base_lr
+ * (the paper does not state a decay shape).  Returns NaN on invalid arguments (non-finite or
+ * negative base_lr / final_ratio). */
+double diloco_lr_at(uint64_t step, uint64_t warmup_steps, uint64_t total_steps, double base_lr,
+                    double final_ratio);
 
 /* The outer step of Figure 1, fused into one launch:
  *   delta_r = theta0 - theta_r            (optionally rounded through binary16)

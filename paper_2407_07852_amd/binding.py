@@ -15,11 +15,12 @@ OK, ROUND_COMPLETE = 0, 1
 ERR_INVALID_ARG, ERR_ALIGN, ERR_ARENA_TOO_SMALL, ERR_HIP, ERR_STATE = -1, -2, -3, -4, -5
 F32, F16 = 0, 1
 BUF_THETA0, BUF_MOM, BUF_THETA, BUF_M, BUF_V = 0, 1, 2, 3, 4
-MAX_WORKERS, TENSOR_ALIGN, TILE = 64, 64, 8192
+MAX_WORKERS, TENSOR_ALIGN, TILE, MAX_GROUPS = 64, 64, 8192, 8
 
 EXPORTS = ["diloco_query_layout", "diloco_init", "diloco_unscale_check", "diloco_inner_step",
            "diloco_outer_step", "diloco_get_buffer", "diloco_get_layout", "diloco_get_steps",
-           "diloco_cast_f32_to_f16", "diloco_set_tuning", "diloco_last_error", "diloco_destroy"]
+           "diloco_cast_f32_to_f16", "diloco_set_tuning", "diloco_last_error", "diloco_destroy",
+           "diloco_set_param_groups", "diloco_lr_at"]
 
 
 class Config(C.Structure):
@@ -67,9 +68,13 @@ def lib():
         L.diloco_last_error.argtypes = [vp]
         L.diloco_last_error.restype = C.c_char_p
         L.diloco_destroy.argtypes = [vp]
+        L.diloco_set_param_groups.argtypes = [vp, C.POINTER(C.c_uint8), u32,
+                                              C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.diloco_lr_at.argtypes = [u64, u64, u64, C.c_double, C.c_double]
         for n in EXPORTS:
-            if n != "diloco_last_error":
+            if n not in ("diloco_last_error", "diloco_lr_at"):
                 getattr(L, n).restype = C.c_int
+        L.diloco_lr_at.restype = C.c_double
         _lib = L
     return _lib
 
@@ -149,6 +154,21 @@ def diloco_set_tuning(ctx, name, value):
     return _check(lib().diloco_set_tuning(ctx, name.encode(), value), ctx)
 
 
+def diloco_set_param_groups(ctx, group_of_tensor, lr_scale, weight_decay):
+    """group_of_tensor: one group id per tensor; lr_scale / weight_decay: one value per group.
+    Empty lists restore the single group of the config."""
+    n = len(lr_scale)
+    assert len(weight_decay) == n
+    got = (C.c_uint8 * max(1, len(group_of_tensor)))(*group_of_tensor)
+    ls = (C.c_double * max(1, n))(*lr_scale)
+    wd = (C.c_double * max(1, n))(*weight_decay)
+    return _check(lib().diloco_set_param_groups(ctx, got, n, ls, wd), ctx)
+
+
+def diloco_lr_at(step, warmup_steps, total_steps, base_lr, final_ratio=1.0):
+    return lib().diloco_lr_at(step, warmup_steps, total_steps, base_lr, final_ratio)
+
+
 def diloco_last_error(ctx=None):
     return lib().diloco_last_error(ctx).decode()
 
@@ -223,6 +243,9 @@ class DiLoCo:
 
     def steps(self):
         return diloco_get_steps(self.ctx, self.k)
+
+    def set_param_groups(self, group_of_tensor, lr_scale, weight_decay):
+        return diloco_set_param_groups(self.ctx, group_of_tensor, lr_scale, weight_decay)
 
     def set_tuning(self, **kw):
         for name, value in kw.items():

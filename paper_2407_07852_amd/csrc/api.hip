@@ -28,6 +28,11 @@ struct diloco_ctx {
   float inv_scale;
   const int32_t* checked_flags;
   const void* checked_grads;
+  // parameter groups
+  uint32_t n_groups;               // 0 = single group from cfg
+  uint8_t* d_chunk_group;          // device, [n_pad / 64]
+  double lr_scale[DILOCO_MAX_GROUPS];
+  double group_wd[DILOCO_MAX_GROUPS];
   Tuning tune;
   std::string err;
 };
@@ -202,9 +207,12 @@ int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco
   c->inv_scale = 1.0f;
   c->checked_flags = nullptr;
   c->checked_grads = nullptr;
+  c->n_groups = 0;
+  c->d_chunk_group = nullptr;
 
   auto bail = [&](int code) {
     if (c->d_state) (void)hipFree(c->d_state);
+    if (c->d_chunk_group) (void)hipFree(c->d_chunk_group);
     g_err = c->err.empty() ? g_err : c->err;
     delete c;
     return code;
@@ -325,8 +333,14 @@ int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
   a.lr_wd = (float)(lr * cf.weight_decay);
   a.eps = (float)cf.eps;
   a.inv_scale = inv_scale;
-  hipError_t e = launch_inner(a, (int)k, grad_dtype == DILOCO_F16, ctx->tune, ctx->n_cu,
-                              ctx->stream);
+  a.chunk_group = ctx->d_chunk_group;
+  for (uint32_t q = 0; q < DILOCO_MAX_GROUPS; ++q) {
+    const bool used = q < ctx->n_groups;
+    a.lr_g[q] = used ? (float)(lr * ctx->lr_scale[q]) : 0.0f;
+    a.lr_wd_g[q] = used ? (float)(lr * ctx->lr_scale[q] * ctx->group_wd[q]) : 0.0f;
+  }
+  hipError_t e = launch_inner(a, (int)k, grad_dtype == DILOCO_F16, ctx->n_groups != 0, ctx->tune,
+                              ctx->n_cu, ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, "inner step launch", e);
   ctx->parity ^= 1;
   ctx->have_scale = false;
@@ -334,6 +348,64 @@ int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
   if (cf.h_inner_steps != 0 && ctx->steps_since_outer % cf.h_inner_steps == 0)
     return DILOCO_ROUND_COMPLETE;
   return DILOCO_OK;
+}
+
+int diloco_set_param_groups(diloco_ctx* ctx, const uint8_t* group_of_tensor, uint32_t n_groups,
+                            const double* lr_scale, const double* weight_decay) {
+  if (!ctx) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "ctx is NULL");
+  if (n_groups == 0) {
+    ctx->n_groups = 0;
+    return DILOCO_OK;
+  }
+  if (n_groups > DILOCO_MAX_GROUPS)
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "n_groups %u exceeds %d", n_groups, DILOCO_MAX_GROUPS);
+  if (!group_of_tensor || !lr_scale || !weight_decay)
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "NULL group table");
+  for (uint32_t q = 0; q < n_groups; ++q)
+    if (!finite_in(lr_scale[q], 0, false, HUGE_VAL, true) ||
+        !finite_in(weight_decay[q], 0, false, HUGE_VAL, true))
+      return fail(ctx, DILOCO_ERR_INVALID_ARG, "group %u: lr_scale and weight_decay must be finite and >= 0", q);
+  const uint32_t nt = ctx->cfg.n_tensors;
+  for (uint32_t t = 0; t < nt; ++t)
+    if (group_of_tensor[t] >= n_groups)
+      return fail(ctx, DILOCO_ERR_INVALID_ARG, "tensor %u: group %u out of range", t,
+                  (unsigned)group_of_tensor[t]);
+  // One group id per 64-element chunk; a chunk never holds elements of two tensors because
+  // every tensor starts on a 64-element boundary.  Chunks of pure padding take group 0.
+  const uint64_t n_chunks = ctx->lay.n_pad / DILOCO_TENSOR_ALIGN;
+  std::vector<uint8_t> map(n_chunks, 0);
+  for (uint32_t t = 0; t < nt; ++t) {
+    const uint64_t first = ctx->offsets[t] / DILOCO_TENSOR_ALIGN;
+    const uint64_t last = (ctx->offsets[t] + ctx->numel[t] - 1) / DILOCO_TENSOR_ALIGN;
+    for (uint64_t c = first; c <= last; ++c) map[c] = group_of_tensor[t];
+  }
+  hipError_t e = hipStreamSynchronize(ctx->stream);  // no launch may still read the old map
+  if (e != hipSuccess) return fail_hip(ctx, "stream synchronize", e);
+  if (!ctx->d_chunk_group) {
+    e = hipMalloc(reinterpret_cast<void**>(&ctx->d_chunk_group), n_chunks);
+    if (e != hipSuccess) return fail_hip(ctx, "hipMalloc(chunk groups)", e);
+  }
+  e = hipMemcpy(ctx->d_chunk_group, map.data(), n_chunks, hipMemcpyHostToDevice);
+  if (e != hipSuccess) return fail_hip(ctx, "chunk group upload", e);
+  for (uint32_t q = 0; q < n_groups; ++q) {
+    ctx->lr_scale[q] = lr_scale[q];
+    ctx->group_wd[q] = weight_decay[q];
+  }
+  ctx->n_groups = n_groups;
+  return DILOCO_OK;
+}
+
+double diloco_lr_at(uint64_t step, uint64_t warmup_steps, uint64_t total_steps, double base_lr,
+                    double final_ratio) {
+  if (!finite_in(base_lr, 0, false, HUGE_VAL, true) ||
+      !finite_in(final_ratio, 0, false, HUGE_VAL, true))
+    return NAN;
+  if (step < warmup_steps) return base_lr * ((double)step / (double)warmup_steps);
+  if (total_steps <= warmup_steps) return base_lr;
+  if (step >= total_steps) return base_lr * final_ratio;
+  const double progress = (double)(step - warmup_steps) / (double)(total_steps - warmup_steps);
+  const double cosine = 0.5 * (1.0 + std::cos(3.14159265358979323846 * progress));
+  return base_lr * (final_ratio + (1.0 - final_ratio) * cosine);
 }
 
 int diloco_outer_step(diloco_ctx* ctx) {
@@ -433,6 +505,10 @@ int diloco_destroy(diloco_ctx* ctx) {
   if (!ctx) return DILOCO_OK;
   hipError_t e = hipStreamSynchronize(ctx->stream);
   hipError_t e2 = hipFree(ctx->d_state);
+  if (ctx->d_chunk_group) {
+    hipError_t e3 = hipFree(ctx->d_chunk_group);
+    if (e2 == hipSuccess) e2 = e3;
+  }
   delete ctx;
   if (e != hipSuccess) return fail_hip(nullptr, "stream synchronize at destroy", e);
   if (e2 != hipSuccess) return fail_hip(nullptr, "hipFree at destroy", e2);

@@ -45,6 +45,10 @@ struct InnerArgs {
   RepState* st_nxt;          // [k]
   double beta1d, beta2d;
   float beta1, beta2, omb1, omb2, lr, lr_wd, eps, inv_scale;
+  // parameter groups (only read by the grouped kernel variant)
+  const uint8_t* chunk_group;  // device, one group id per 64-element chunk
+  float lr_g[8];
+  float lr_wd_g[8];
 };
 
 struct OuterArgs {
@@ -58,8 +62,8 @@ struct OuterArgs {
   int f16;
 };
 
-hipError_t launch_inner(const InnerArgs& a, int k, bool g16, const Tuning& t, int n_cu,
-                        hipStream_t s);
+hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const Tuning& t,
+                        int n_cu, hipStream_t s);
 hipError_t launch_outer(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s);
 hipError_t launch_check(const void* g, uint64_t g_stride, uint64_t n_pad, int k, bool g16,
                         int32_t* found_inf, const Tuning& t, int n_cu, hipStream_t s);

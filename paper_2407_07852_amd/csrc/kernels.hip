@@ -57,18 +57,19 @@ __device__ __forceinline__ uint32_t tile_of_block(int xcd_remap) {
 // (Section "Implementation": the inner optimizer is AdamW, one step per training step.)
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void adamw_elem(float& th, float& m, float& v, float g,
-                                           const InnerArgs& a, float bc1, float bc2) {
+                                           const InnerArgs& a, float lr, float lr_wd, float bc1,
+                                           float bc2) {
   const float mi = a.beta1 * m + a.omb1 * g;
   const float vi = a.beta2 * v + a.omb2 * (g * g);
   const float m_hat = mi / bc1;
   const float v_hat = vi / bc2;
-  const float decayed = th - a.lr_wd * th;
-  th = decayed - a.lr * (m_hat / (sqrtf(v_hat) + a.eps));
+  const float decayed = th - lr_wd * th;
+  th = decayed - lr * (m_hat / (sqrtf(v_hat) + a.eps));
   m = mi;
   v = vi;
 }
 
-template <int B, int V, bool G16, bool NT>
+template <int B, int V, bool G16, bool NT, bool GROUPS>
 __global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32_t tiles,
                                                        int xcd_remap) {
   const uint32_t r = blockIdx.y;
@@ -89,6 +90,7 @@ __global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32
   const size_t base = (size_t)tile * (B * V) + threadIdx.x;
   f32x4 th[V], m[V], v[V], g[V];
   u32x2 graw[V];
+  uint8_t grp[V];
 #pragma unroll
   for (int j = 0; j < V; ++j) {
     const size_t i = base + (size_t)j * B;
@@ -97,6 +99,8 @@ __global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32
     th[j] = ld<NT>(th_p + i);
     m[j] = ld<NT>(m_p + i);
     v[j] = ld<NT>(v_p + i);
+    // A lane's four elements lie inside one 64-element chunk, and a chunk holds one tensor.
+    if constexpr (GROUPS) grp[j] = a.chunk_group[i >> 4];
   }
 
   // Worker r's step state.  A worker whose found_inf flag is set takes no step at all: its
@@ -120,10 +124,21 @@ __global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32
       __builtin_memcpy(&h, &graw[j], 8);
       g[j] = __builtin_convertvector(h, f32x4) * a.inv_scale;
     }
+    float lr = a.lr, lr_wd = a.lr_wd;
+    if constexpr (GROUPS) {
+      // select the group's scalars (they sit in SGPRs; at most 8 groups)
+      lr = a.lr_g[0];
+      lr_wd = a.lr_wd_g[0];
+#pragma unroll
+      for (int q = 1; q < 8; ++q) {
+        lr = grp[j] == q ? a.lr_g[q] : lr;
+        lr_wd = grp[j] == q ? a.lr_wd_g[q] : lr_wd;
+      }
+    }
 #pragma unroll
     for (int c = 0; c < kVecElems; ++c) {
       float t = th[j][c], mm = m[j][c], vv = v[j][c];
-      adamw_elem(t, mm, vv, g[j][c], a, bc1, bc2);
+      adamw_elem(t, mm, vv, g[j][c], a, lr, lr_wd, bc1, bc2);
       th[j][c] = t;
       m[j][c] = mm;
       v[j][c] = vv;
@@ -365,12 +380,12 @@ uint32_t grid_x(uint64_t tiles, int persist, int n_cu, bool xcd_remap) {
 // ------------------------------------------------------------------------------------------
 // Launchers.  n_pad is a multiple of 8192 elements, so every tile size below divides it.
 // ------------------------------------------------------------------------------------------
-template <int B, int V, bool G16, bool NT>
+template <int B, int V, bool G16, bool NT, bool GROUPS>
 static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int n_cu,
                                  hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
   const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0), (uint32_t)k);
-  hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT>), grid, dim3(B),
+  hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT, GROUPS>), grid, dim3(B),
                      pad_lds_bytes(t.inner_waves < 0 ? auto_waves((G16 ? 3584 : 4096) * V) : t.inner_waves, B,
                                    t.lds_per_cu),
                      s, a, (uint32_t)tiles,
@@ -378,32 +393,39 @@ static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int
   return hipGetLastError();
 }
 
-template <int B, bool G16, bool NT>
+template <int B, bool G16, bool NT, bool GROUPS>
 static hipError_t launch_inner_b(const InnerArgs& a, int k, const Tuning& t, int n_cu,
                                  hipStream_t s) {
   switch (t.inner_vec) {
-    case 2: return launch_inner_t<B, 2, G16, NT>(a, k, t, n_cu, s);
-    case 4: return launch_inner_t<B, 4, G16, NT>(a, k, t, n_cu, s);
-    default: return launch_inner_t<B, 1, G16, NT>(a, k, t, n_cu, s);
+    case 2: return launch_inner_t<B, 2, G16, NT, GROUPS>(a, k, t, n_cu, s);
+    case 4: return launch_inner_t<B, 4, G16, NT, GROUPS>(a, k, t, n_cu, s);
+    default: return launch_inner_t<B, 1, G16, NT, GROUPS>(a, k, t, n_cu, s);
   }
 }
 
-template <bool G16, bool NT>
+template <bool G16, bool NT, bool GROUPS>
 static hipError_t launch_inner_v(const InnerArgs& a, int k, const Tuning& t, int n_cu,
                                  hipStream_t s) {
   switch (t.inner_block) {
-    case 128: return launch_inner_b<128, G16, NT>(a, k, t, n_cu, s);
-    case 256: return launch_inner_b<256, G16, NT>(a, k, t, n_cu, s);
-    default: return launch_inner_b<64, G16, NT>(a, k, t, n_cu, s);
+    case 128: return launch_inner_b<128, G16, NT, GROUPS>(a, k, t, n_cu, s);
+    case 256: return launch_inner_b<256, G16, NT, GROUPS>(a, k, t, n_cu, s);
+    default: return launch_inner_b<64, G16, NT, GROUPS>(a, k, t, n_cu, s);
   }
 }
 
-hipError_t launch_inner(const InnerArgs& a, int k, bool g16, const Tuning& t, int n_cu,
-                        hipStream_t s) {
-  if (g16) return t.inner_nt ? launch_inner_v<true, true>(a, k, t, n_cu, s)
-                             : launch_inner_v<true, false>(a, k, t, n_cu, s);
-  return t.inner_nt ? launch_inner_v<false, true>(a, k, t, n_cu, s)
-                    : launch_inner_v<false, false>(a, k, t, n_cu, s);
+template <bool G16, bool GROUPS>
+static hipError_t launch_inner_n(const InnerArgs& a, int k, const Tuning& t, int n_cu,
+                                 hipStream_t s) {
+  return t.inner_nt ? launch_inner_v<G16, true, GROUPS>(a, k, t, n_cu, s)
+                    : launch_inner_v<G16, false, GROUPS>(a, k, t, n_cu, s);
+}
+
+hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const Tuning& t,
+                        int n_cu, hipStream_t s) {
+  if (groups) return g16 ? launch_inner_n<true, true>(a, k, t, n_cu, s)
+                         : launch_inner_n<false, true>(a, k, t, n_cu, s);
+  return g16 ? launch_inner_n<true, false>(a, k, t, n_cu, s)
+             : launch_inner_n<false, false>(a, k, t, n_cu, s);
 }
 
 template <int B, int K, int V, bool F16, bool NT>

@@ -63,6 +63,9 @@ class GpuSide:
     def host(self, t):
         return t.detach().cpu().numpy()
 
+    def set_groups(self, group_of_tensor, lr_scale, weight_decay):
+        self.dl.set_param_groups(list(group_of_tensor), list(lr_scale), list(weight_decay))
+
 
 class CpuSide:
     """The oracle on the same workload, inputs generated on the host."""
@@ -77,6 +80,10 @@ class CpuSide:
         self.o = oracle.DiLoCoOracle(theta0, k, hp["inner_lr"], hp["beta1"], hp["beta2"],
                                      hp["eps"], hp["weight_decay"], hp["outer_lr"],
                                      hp["outer_momentum"], pg_f16)
+
+    def set_groups(self, group_of_tensor, lr_scale, weight_decay):
+        self.o.groups = oracle.ParamGroups(self.offsets, self.wl.numel, group_of_tensor, lr_scale,
+                                           weight_decay)
 
     def gen_grads(self, step, f16=False, inject_replica=None, inject_period=0):
         out = []
@@ -154,9 +161,31 @@ class SampledCpuSide:
                                      hp["eps"], hp["weight_decay"], hp["outer_lr"],
                                      hp["outer_momentum"], pg_f16)
 
+        self.tensor_at = t
+
+    def set_groups(self, group_of_tensor, lr_scale, weight_decay):
+        """Groups for a sampled index set: self.idx must have been ordered with
+        order_by_group() so that each group's samples are one contiguous run."""
+        g = np.asarray(group_of_tensor, dtype=np.uint8)[self.tensor_at]
+        cuts = np.flatnonzero(np.diff(g.astype(np.int64))) + 1
+        starts = np.concatenate([[0], cuts]).astype(np.uint64)
+        lens = np.diff(np.concatenate([starts, [g.size]]).astype(np.int64)).astype(np.uint64)
+        assert len(starts) <= len(lr_scale), "samples are not ordered by group"
+        self.o.groups = oracle.ParamGroups(starts, lens, g[starts.astype(np.int64)], lr_scale,
+                                           weight_decay)
+
     def gen_grads(self, step):
         return [synth.host_gather_f32(self.idx, synth.key(synth.STREAM_GRADS, r, step), G_SIGMA,
                                       self.kind_at) for r in range(self.k)]
+
+
+def order_by_group(idx, offsets, group_of_tensor):
+    """Reorders flat indices so that those of the same parameter group are contiguous (pads
+    count with the tensor before them, as the library's 64-element chunks do)."""
+    idx = np.asarray(idx, dtype=np.uint64)
+    t = np.searchsorted(np.asarray(offsets, dtype=np.uint64), idx, side="right") - 1
+    g = np.asarray(group_of_tensor)[t]
+    return idx[np.argsort(g, kind="stable")]
 
 
 def gather_gpu(gpu, t, idx_dev):

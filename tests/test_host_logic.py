@@ -135,3 +135,13 @@ def test_generator_host_twin_against_python():
     assert abs(float(x.std()) - 1e-3) < 2e-5 and abs(float(x.mean())) < 5e-6
     assert np.array_equal(synth.host_fill_f32(1000, k, 1e-3, first=77), synth.host_gather_f32(
         np.arange(77, 1077, dtype=np.uint64), k, 1e-3))
+
+
+def test_lr_schedule_matches_oracle():
+    D = _D()
+    for warm, total, ratio in ((1000, 0, 1.0), (1000, 88000, 0.1), (0, 100, 0.0), (5, 5, 0.5)):
+        for step in list(range(0, 20)) + [999, 1000, 1001, 44000, 87999, 88000, 10 ** 7]:
+            assert D.diloco_lr_at(step, warm, total, 4e-4, ratio) == oracle.lr_at(step, warm, total,
+                                                                                  4e-4, ratio)
+    assert np.isnan(D.diloco_lr_at(1, 10, 0, -1.0, 1.0))
+    assert np.isnan(D.diloco_lr_at(1, 10, 0, float("inf"), 1.0))
