@@ -46,7 +46,7 @@ extern __shared__ float occupancy_pad[];
 // any grid-stride variant).  With xcd_remap the hardware's round-robin of consecutive
 // workgroups over the 8 XCDs is undone so that each XCD walks one contiguous range of tiles
 // (gridDim.x is then a multiple of 8 and may exceed the tile count).
-__device__ __forceinline__ uint32_t tile_of_block(int xcd_remap) {
+__device__ __forceinline__ uint32_t tile_of_block(bool xcd_remap) {
   const uint32_t b = blockIdx.x;
   if (!xcd_remap) return b;
   return (b % kXcds) * (gridDim.x / kXcds) + b / kXcds;
@@ -69,13 +69,15 @@ __device__ __forceinline__ void adamw_elem(float& th, float& m, float& v, float 
   v = vi;
 }
 
-template <int B, int V, bool G16, bool NT, bool GROUPS>
-__global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32_t tiles,
-                                                       int xcd_remap) {
+template <int B, int V, bool G16, bool NT, bool GROUPS, bool REMAP>
+__global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32_t tiles) {
   const uint32_t r = blockIdx.y;
-  const uint32_t tile = tile_of_block(xcd_remap);
-  if (tile >= tiles) return;
-  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // keeps the LDS pad allocated
+  // Without the XCD remap the grid holds exactly one workgroup per tile: no bounds check, so
+  // the first vector loads wait for a single batch of kernel-argument loads only.
+  const uint32_t tile = tile_of_block(REMAP);
+  if constexpr (REMAP) {
+    if (tile >= tiles) return;
+  }
 
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta + (size_t)r * a.stride);
   f32x4* __restrict__ m_p = reinterpret_cast<f32x4*>(a.m + (size_t)r * a.stride);
@@ -100,7 +102,17 @@ __global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32
     m[j] = ld<NT>(m_p + i);
     v[j] = ld<NT>(v_p + i);
     // A lane's four elements lie inside one 64-element chunk, and a chunk holds one tensor.
-    if constexpr (GROUPS) grp[j] = a.chunk_group[i >> 4];
+    // With single-wave workgroups a row of the tile is 4 chunks = one 32-bit word of the chunk
+    // map at a wave-uniform address: a scalar load, no extra vector memory instruction.
+    if constexpr (GROUPS) {
+      if constexpr (B == 64) {
+        const uint32_t word =
+            reinterpret_cast<const uint32_t*>(a.chunk_group)[(size_t)tile * V + j];
+        grp[j] = (uint8_t)(word >> ((threadIdx.x >> 4) * 8));
+      } else {
+        grp[j] = a.chunk_group[i >> 4];
+      }
+    }
   }
 
   // Worker r's step state.  A worker whose found_inf flag is set takes no step at all: its
@@ -151,6 +163,7 @@ __global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32
     st<NT>(m_p + i, m[j]);
     st<NT>(v_p + i, v[j]);
   }
+  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
 // ------------------------------------------------------------------------------------------
@@ -172,12 +185,12 @@ __device__ __forceinline__ void nesterov_elem(float& th0, float& b, float dbar, 
   b = bn;
 }
 
-template <int B, int K, int V, bool F16, bool NT>
-__global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint32_t tiles,
-                                                        int xcd_remap) {
-  const uint32_t tile = tile_of_block(xcd_remap);
-  if (tile >= tiles) return;
-  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // keeps the LDS pad allocated
+template <int B, int K, int V, bool F16, bool NT, bool REMAP>
+__global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint32_t tiles) {
+  const uint32_t tile = tile_of_block(REMAP);
+  if constexpr (REMAP) {
+    if (tile >= tiles) return;
+  }
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
@@ -214,14 +227,13 @@ __global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint3
 #pragma unroll
     for (int r = 0; r < K; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0[j]);
   }
+  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
 // Any k (run-time loop over the workers): one single-wave workgroup per 256-element tile.
 template <bool F16, bool NT>
 __global__ __launch_bounds__(64) void outer_fused_anyk_kernel(const OuterArgs a, uint32_t tiles) {
-  const uint32_t tile = blockIdx.x;
-  if (tile >= tiles) return;
-  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // keeps the LDS pad allocated
+  const uint32_t tile = blockIdx.x;  // the grid holds exactly one workgroup per tile
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
@@ -252,6 +264,7 @@ __global__ __launch_bounds__(64) void outer_fused_anyk_kernel(const OuterArgs a,
   st<NT>(t0_p + i, t0);
   st<NT>(b_p + i, b);
   for (int r = 0; r < a.k; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0);
+  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
 // ------------------------------------------------------------------------------------------
@@ -385,11 +398,16 @@ static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int
                                  hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
   const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0), (uint32_t)k);
-  hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT, GROUPS>), grid, dim3(B),
-                     pad_lds_bytes(t.inner_waves < 0 ? auto_waves((G16 ? 3584 : 4096) * V) : t.inner_waves, B,
-                                   t.lds_per_cu),
-                     s, a, (uint32_t)tiles,
-                     t.xcd_remap);
+  // The grouped variant's tile waits for one more dependent scalar load: 3 more waves.
+  const int waves = t.inner_waves < 0 ? auto_waves((G16 ? 3584 : 4096) * V) + (GROUPS ? 3 : 0)
+                                      : t.inner_waves;
+  const uint32_t lds = pad_lds_bytes(waves, B, t.lds_per_cu);
+  if (t.xcd_remap)
+    hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT, GROUPS, true>), grid, dim3(B), lds, s, a,
+                       (uint32_t)tiles);
+  else
+    hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT, GROUPS, false>), grid, dim3(B), lds, s,
+                       a, (uint32_t)tiles);
   return hipGetLastError();
 }
 
@@ -432,11 +450,14 @@ template <int B, int K, int V, bool F16, bool NT>
 static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
   const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0));
-  hipLaunchKernelGGL((outer_fused_kernel<B, K, V, F16, NT>), grid, dim3(B),
-                     pad_lds_bytes(t.outer_waves < 0 ? auto_waves((K + 2) * 1024 * V) : t.outer_waves, B,
-                                   t.lds_per_cu),
-                     s, a, (uint32_t)tiles,
-                     t.xcd_remap);
+  const uint32_t lds = pad_lds_bytes(
+      t.outer_waves < 0 ? auto_waves((K + 2) * 1024 * V) : t.outer_waves, B, t.lds_per_cu);
+  if (t.xcd_remap)
+    hipLaunchKernelGGL((outer_fused_kernel<B, K, V, F16, NT, true>), grid, dim3(B), lds, s, a,
+                       (uint32_t)tiles);
+  else
+    hipLaunchKernelGGL((outer_fused_kernel<B, K, V, F16, NT, false>), grid, dim3(B), lds, s, a,
+                       (uint32_t)tiles);
   return hipGetLastError();
 }
 
