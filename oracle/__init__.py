@@ -42,7 +42,12 @@ def lib():
             "oracle_replica_mean_f64": (None, [vp, sz, sz, vp]),
             "oracle_nesterov_step_f32": (None, [vp, vp, vp, sz, f64, f64]),
             "oracle_nesterov_step_f64": (None, [vp, vp, vp, sz, f64, f64]),
-            "oracle_outer_step_f32": (None, [vp, vp, vp, sz, sz, f64, f64, i32, vp, vp]),
+            "oracle_outer_step_f32": (None, [vp, vp, vp, sz, sz, f64, f64, i32, i32, vp, vp]),
+            "oracle_f32_to_bf16_rne": (u16, [f32]),
+            "oracle_bf16_to_f32": (f32, [u16]),
+            "oracle_cast_f32_to_bf16": (None, [vp, vp, sz]),
+            "oracle_cast_pattern_range_bf16": (None, [u32, sz, vp]),
+            "oracle_round_through_bf16": (None, [vp, sz]),
             "oracle_plan_layout": (u64, [vp, u32, u64, u64, vp]),
             "oracle_num_threads": (C.c_int, []),
         }
@@ -74,6 +79,34 @@ def cast_pattern_range(first, n):
     out = np.empty(n, dtype=np.uint16)
     lib().oracle_cast_pattern_range(int(first) & 0xFFFFFFFF, n, _p(out, np.uint16))
     return out
+
+
+def f32_to_bf16_bits(x):
+    """RNE cast of a float32 array to bfloat16 bit patterns (uint16)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    lib().oracle_cast_f32_to_bf16(_p(x, np.float32), _p(out, np.uint16), x.size)
+    return out
+
+
+def cast_pattern_range_bf16(first, n):
+    out = np.empty(n, dtype=np.uint16)
+    lib().oracle_cast_pattern_range_bf16(int(first) & 0xFFFFFFFF, n, _p(out, np.uint16))
+    return out
+
+
+def bf16_bits_to_f32(h):
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    return np.array([lib().oracle_bf16_to_f32(int(x)) for x in h.reshape(-1)],
+                    dtype=np.float32).reshape(h.shape)
+
+
+PG_F32, PG_F16, PG_BF16 = 0, 1, 2
+
+
+def _pg_code(pg):
+    """Accepts the historical bool (False = FP32, True = FP16) or a PG_* code."""
+    return {False: PG_F32, True: PG_F16}.get(pg, pg) if isinstance(pg, bool) else int(pg)
 
 
 def f16_bits_to_f32(h):
@@ -186,15 +219,16 @@ def nesterov_step(theta0, b, grad, lr, mu):
     fn(_p(theta0, dt), _p(b, dt), _p(grad, dt), theta0.size, lr, mu)
 
 
-def outer_step(theta0, b, theta, outer_lr, mu, pg_f16, scratch=None):
-    """Whole outer step, float32, in place.  theta is [k][n].  scratch: optional preallocated
-    (delta[k][n], mean[n]) work arrays."""
+def outer_step(theta0, b, theta, outer_lr, mu, pg_f16, scratch=None, round_mean=False):
+    """Whole outer step, float32, in place.  theta is [k][n].  pg_f16: False/True or a PG_* code
+    (type the pseudo-gradients are rounded through); round_mean: also round the average.
+    scratch: optional preallocated (delta[k][n], mean[n]) work arrays."""
     k, n = theta.shape
     d, mean = scratch if scratch is not None else (np.empty((k, n), dtype=np.float32),
                                                    np.empty(n, dtype=np.float32))
     lib().oracle_outer_step_f32(_p(theta0, np.float32), _p(b, np.float32), _p(theta, np.float32),
-                                k, n, outer_lr, mu, 1 if pg_f16 else 0, _p(d, np.float32),
-                                _p(mean, np.float32))
+                                k, n, outer_lr, mu, _pg_code(pg_f16), 1 if round_mean else 0,
+                                _p(d, np.float32), _p(mean, np.float32))
     return mean
 
 
@@ -218,11 +252,12 @@ class DiLoCoOracle:
     skips its inner step entirely (weights, moments and step count stay as they are)."""
 
     def __init__(self, theta_init, k, inner_lr, beta1, beta2, eps, weight_decay, outer_lr,
-                 outer_momentum, pg_f16=False):
+                 outer_momentum, pg_f16=False, round_mean=False):
         theta_init = np.ascontiguousarray(theta_init, dtype=np.float32).reshape(-1)
         self.k = k
         self.hp = (inner_lr, beta1, beta2, eps, weight_decay)
         self.outer_lr, self.mu, self.pg_f16 = outer_lr, outer_momentum, pg_f16
+        self.round_mean = round_mean
         self.theta0 = theta_init.copy()
         self.b = np.zeros_like(self.theta0)
         self.workers = [AdamWState(theta_init) for _ in range(k)]
@@ -244,7 +279,8 @@ class DiLoCoOracle:
 
     def outer_step(self):
         theta = np.stack([st.theta for st in self.workers])
-        mean = outer_step(self.theta0, self.b, theta, self.outer_lr, self.mu, self.pg_f16)
+        mean = outer_step(self.theta0, self.b, theta, self.outer_lr, self.mu, self.pg_f16,
+                          round_mean=self.round_mean)
         for r, st in enumerate(self.workers):
             st.theta[:] = theta[r]
         return mean

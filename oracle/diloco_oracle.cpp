@@ -93,6 +93,24 @@ float f16_to_f32(uint16_t h) {
 }
 
 // ---------------------------------------------------------------------------
+// bfloat16 = the upper 16 bits of a binary32 (1 sign, 8 exponent, 7 fraction bits), reached by
+// round to nearest, ties to even, on the dropped 16 bits.  Same exponent range as binary32, so
+// subnormals round on the same grid and only values within half a unit of the largest finite
+// bfloat16 of binary32's top binade overflow to infinity.
+// ---------------------------------------------------------------------------
+uint16_t f32_to_bf16_rne(float f) {
+  const uint32_t u = bits_of(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
+  const uint32_t keep = u >> 16;
+  const uint32_t rem = u & 0xffffu;
+  uint32_t out = keep;
+  if (rem > 0x8000u || (rem == 0x8000u && (keep & 1u))) out += 1;  // carry may reach infinity
+  return (uint16_t)out;
+}
+
+float bf16_to_f32(uint16_t h) { return float_of((uint32_t)h << 16); }
+
+// ---------------------------------------------------------------------------
 // Inner optimizer: one AdamW step of one worker over n elements.
 // p1, p2 are the worker's running products beta1^t, beta2^t (double, start 1);
 // the step advances them, i.e. the worker's step count t grows by one.
@@ -209,6 +227,19 @@ void oracle_cast_f16_to_f32(const uint16_t* in, float* out, size_t n) {
   for (size_t i = 0; i < n; ++i) out[i] = f16_to_f32(in[i]);
 }
 
+uint16_t oracle_f32_to_bf16_rne(float f) { return f32_to_bf16_rne(f); }
+float oracle_bf16_to_f32(uint16_t h) { return bf16_to_f32(h); }
+
+void oracle_cast_f32_to_bf16(const float* in, uint16_t* out, size_t n) {
+#pragma omp parallel for schedule(static)
+  for (size_t i = 0; i < n; ++i) out[i] = f32_to_bf16_rne(in[i]);
+}
+
+void oracle_cast_pattern_range_bf16(uint32_t first, size_t n, uint16_t* out) {
+#pragma omp parallel for schedule(static)
+  for (size_t i = 0; i < n; ++i) out[i] = f32_to_bf16_rne(float_of(first + (uint32_t)i));
+}
+
 // ---- inner step ------------------------------------------------------------
 void oracle_adamw_step_f32(float* theta, float* m, float* v, const float* g, size_t n, double lr,
                            double beta1, double beta2, double eps, double weight_decay,
@@ -291,6 +322,18 @@ void oracle_round_through_f16(float* delta, size_t n) {
   for (size_t i = 0; i < n; ++i) delta[i] = f16_to_f32(f32_to_f16_rne(delta[i]));
 }
 
+// In place: delta <- widen(bf16_rne(delta)).
+void oracle_round_through_bf16(float* delta, size_t n) {
+#pragma omp parallel for schedule(static)
+  for (size_t i = 0; i < n; ++i) delta[i] = bf16_to_f32(f32_to_bf16_rne(delta[i]));
+}
+
+// pg_dtype: 0 = binary32 (no rounding), 1 = binary16, 2 = bfloat16.
+static void round_through(float* x, size_t n, int32_t pg_dtype) {
+  if (pg_dtype == 1) oracle_round_through_f16(x, n);
+  if (pg_dtype == 2) oracle_round_through_bf16(x, n);
+}
+
 void oracle_replica_mean_f32(const float* delta, size_t k, size_t n, float* mean) {
   replica_mean<float>(delta, k, n, mean);
 }
@@ -308,16 +351,19 @@ void oracle_nesterov_step_f64(double* theta0, double* b, const double* grad, siz
 }
 
 // The whole outer step in Figure 1's order.  theta is [k][n] (the workers' local
-// weights), delta_scratch is [k][n] and mean_scratch is [n].  pg_f16 != 0 rounds
-// each worker's pseudo-gradient through binary16 before the average.
+// weights), delta_scratch is [k][n] and mean_scratch is [n].  pg_dtype (0 binary32,
+// 1 binary16, 2 bfloat16) is the type each worker's pseudo-gradient is rounded through
+// before the average; with round_mean != 0 the average itself is rounded through that type
+// as well, as the output buffer of a reduced-precision all-reduce would be.
 void oracle_outer_step_f32(float* theta0, float* b, float* theta, size_t k, size_t n,
-                           double outer_lr, double mu, int32_t pg_f16, float* delta_scratch,
-                           float* mean_scratch) {
+                           double outer_lr, double mu, int32_t pg_dtype, int32_t round_mean,
+                           float* delta_scratch, float* mean_scratch) {
   for (size_t r = 0; r < k; ++r) {
     pseudo_grad<float>(theta0, theta + r * n, delta_scratch + r * n, n);
-    if (pg_f16) oracle_round_through_f16(delta_scratch + r * n, n);
+    round_through(delta_scratch + r * n, n, pg_dtype);
   }
   replica_mean<float>(delta_scratch, k, n, mean_scratch);
+  if (round_mean) round_through(mean_scratch, n, pg_dtype);
   nesterov_step<float>(theta0, b, mean_scratch, n, outer_lr, mu);
   for (size_t r = 0; r < k; ++r) std::memcpy(theta + r * n, theta0, n * sizeof(float));
 }
