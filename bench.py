@@ -116,6 +116,38 @@ def run_workload(name, k, H, pg_f16, rounds, warmup, torch, D, synth, groups=Fal
     }
 
 
+def quick_measure(name, k, pg_dtype, round_mean, n_inner, n_outer, torch, D, synth):
+    """Short timing of both kernels for one (workload, k, pseudo-gradient mode): n_inner inner
+    launches and n_outer outer launches after two warm-up launches of each."""
+    wl = synth.WORKLOADS[name]()
+    n = wl.n_params
+    stream = torch.cuda.current_stream()
+    dl = D.DiLoCo(wl.numel, k, fill_theta0=lambda t, lay, off: t.normal_(0, 0.02),
+                  pg_dtype=pg_dtype, pg_round_mean=round_mean)
+    g = dl.new_grads()
+    g.normal_(0, 1e-3)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for _ in range(2):
+        dl.inner_step(g)
+        dl.outer_step()
+    torch.cuda.synchronize()
+    ev[0].record(stream)
+    for _ in range(n_inner):
+        dl.inner_step(g)
+    ev[1].record(stream)
+    for _ in range(n_outer):
+        dl.outer_step()
+    ev[2].record(stream)
+    torch.cuda.synchronize()
+    im, om = ev[0].elapsed_time(ev[1]) / n_inner, ev[1].elapsed_time(ev[2]) / n_outer
+    dl.close()
+    del dl, g
+    torch.cuda.empty_cache()
+    ib, ob = inner_bytes(n, k), outer_bytes(n, k)
+    return {"inner_ms": im, "inner_GBps": ib / im / 1e6, "inner_frac": ib / im / 1e6 / HBM_PEAK_GBS,
+            "outer_ms": om, "outer_GBps": ob / om / 1e6, "outer_frac": ob / om / 1e6 / HBM_PEAK_GBS}
+
+
 def run_mixed_precision(k, reps, torch, D, synth):
     """Rows a1 + a2 in mixed precision: binary16 gradients scaled by 65536 on the 150M set plus
     2000 ragged tensors; the inf/NaN check, then the inner step with the unscale fused in."""
@@ -308,6 +340,17 @@ def main():
     if not args.no_also and args.workload == "llama150m":
         out["mixed_precision"] = run_mixed_precision(4, 20, torch, D, synth)
         pgr = run_workload("llama150m", args.k, 100, False, 1, 0, torch, D, synth, groups=True)
+        # worker-count sweep of the paper's ablation (1, 2, 4, 8 workers) and the
+        # reduced-precision pseudo-gradient modes, short timings on the 150M set
+        out["k_sweep"] = {"workload": "llama150m, FP32 pseudo-gradient, 40 inner + 20 outer launches",
+                          **{"k=%d" % kk: quick_measure("llama150m", kk, D.F32, 0, 40, 20, torch, D, synth)
+                             for kk in (1, 2, 4, 8)}}
+        out["pg_modes"] = {"workload": "llama150m x 8 workers, outer step only, 20 launches",
+                           **{nm: {kq: v for kq, v in quick_measure("llama150m", 8, pg, rm, 1, 20, torch, D,
+                                                                     synth).items() if kq.startswith("outer")}
+                              for nm, pg, rm in (("f32", D.F32, 0), ("f16", D.F16, 0),
+                                                 ("f16+rounded_mean", D.F16, 1), ("bf16", D.BF16, 0),
+                                                 ("bf16+rounded_mean", D.BF16, 1))}}
         out["param_groups"] = {
             "config": {"workload": "llama150m x %d workers, 100 inner steps, 3 parameter groups "
                                    "(norm vectors and embedding exempt from weight decay)" % args.k},

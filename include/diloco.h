@@ -52,7 +52,7 @@ enum {
   DILOCO_ERR_STATE = -5            /* call sequence error (e.g. flags passed without a check) */
 };
 
-enum { DILOCO_F32 = 0, DILOCO_F16 = 1 }; /* element type of pseudo-gradients / gradients */
+enum { DILOCO_F32 = 0, DILOCO_F16 = 1, DILOCO_BF16 = 2 }; /* pseudo-gradient types; gradients: F32 or F16 */
 
 enum { /* diloco_get_buffer selector */
   DILOCO_BUF_THETA0 = 0, /* outer weights theta(t), [n_pad] */
@@ -82,9 +82,13 @@ typedef struct {
   double weight_decay;      /* >= 0 (decoupled) */
   double outer_lr;          /* Nesterov SGD: >= 0, finite */
   double outer_momentum;    /* in [0, 1) */
-  int32_t pg_dtype;         /* DILOCO_F32, or DILOCO_F16: round each worker's pseudo-gradient to
-                               IEEE binary16 (nearest-even, subnormals kept, overflow to inf) and
-                               widen it back before the FP32 average */
+  int32_t pg_dtype;         /* DILOCO_F32, or DILOCO_F16 / DILOCO_BF16: round each worker's
+                               pseudo-gradient to IEEE binary16 / bfloat16 (nearest-even,
+                               subnormals kept, overflow to inf) and widen it back before the
+                               FP32 average */
+  int32_t pg_round_mean;    /* 0: the average stays FP32 (default).  1: the average is rounded
+                               through pg_dtype as well, as the output of an all-reduce whose
+                               buffer has that type would be (no effect with DILOCO_F32) */
   void* arena;              /* device, caller-owned, 256-byte aligned; unused by query_layout */
   uint64_t arena_bytes;
   void* stream;             /* hipStream_t, borrowed; NULL = the default stream */
@@ -154,8 +158,9 @@ double diloco_lr_at(uint64_t step, uint64_t warmup_steps, uint64_t total_steps, 
                     double final_ratio);
 
 /* The outer step of Figure 1, fused into one launch:
- *   delta_r = theta0 - theta_r            (optionally rounded through binary16)
- *   dbar    = (delta_0 + ... + delta_{k-1}) / k        (FP32, workers in ascending order)
+ *   delta_r = theta0 - theta_r            (optionally rounded through binary16 / bfloat16)
+ *   dbar    = (delta_0 + ... + delta_{k-1}) / k        (FP32, workers in ascending order;
+ *                                                       rounded too when pg_round_mean is set)
  *   mom     = mu*mom + dbar ;  theta0 = theta0 - outer_lr*(dbar + mu*mom)
  *   theta_r = theta0 for every r.
  * AdamW moments and step counts are not touched.  Legal after any number of inner steps,
@@ -173,6 +178,7 @@ int diloco_get_steps(diloco_ctx* ctx, uint32_t* steps);
 /* The pseudo-gradient's FP32 -> binary16 rounding on its own, as the outer step applies it
  * (Section "All-Reduce in FP16"): in/out are device arrays of n elements (out: uint16 codes). */
 int diloco_cast_f32_to_f16(const float* in, uint16_t* out, uint64_t n, void* stream);
+int diloco_cast_f32_to_bf16(const float* in, uint16_t* out, uint64_t n, void* stream);
 
 /* Launch-shape knobs for benchmarking sweeps; results never depend on them.  Unknown names
  * return DILOCO_ERR_INVALID_ARG. */

@@ -13,14 +13,14 @@ LIB_PATH = os.path.join(HERE, "libdiloco_hip.so")
 
 OK, ROUND_COMPLETE = 0, 1
 ERR_INVALID_ARG, ERR_ALIGN, ERR_ARENA_TOO_SMALL, ERR_HIP, ERR_STATE = -1, -2, -3, -4, -5
-F32, F16 = 0, 1
+F32, F16, BF16 = 0, 1, 2
 BUF_THETA0, BUF_MOM, BUF_THETA, BUF_M, BUF_V = 0, 1, 2, 3, 4
 MAX_WORKERS, TENSOR_ALIGN, TILE, MAX_GROUPS = 64, 64, 8192, 8
 
 EXPORTS = ["diloco_query_layout", "diloco_init", "diloco_unscale_check", "diloco_inner_step",
            "diloco_outer_step", "diloco_get_buffer", "diloco_get_layout", "diloco_get_steps",
            "diloco_cast_f32_to_f16", "diloco_set_tuning", "diloco_last_error", "diloco_destroy",
-           "diloco_set_param_groups", "diloco_lr_at"]
+           "diloco_set_param_groups", "diloco_lr_at", "diloco_cast_f32_to_bf16"]
 
 
 class Config(C.Structure):
@@ -29,7 +29,7 @@ class Config(C.Structure):
                 ("inner_lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
                 ("eps", C.c_double), ("weight_decay", C.c_double),
                 ("outer_lr", C.c_double), ("outer_momentum", C.c_double),
-                ("pg_dtype", C.c_int32), ("arena", C.c_void_p), ("arena_bytes", C.c_uint64),
+                ("pg_dtype", C.c_int32), ("pg_round_mean", C.c_int32), ("arena", C.c_void_p), ("arena_bytes", C.c_uint64),
                 ("stream", C.c_void_p)]
 
 
@@ -64,6 +64,7 @@ def lib():
         L.diloco_get_layout.argtypes = [vp, C.POINTER(Layout)]
         L.diloco_get_steps.argtypes = [vp, C.POINTER(u32)]
         L.diloco_cast_f32_to_f16.argtypes = [vp, vp, u64, vp]
+        L.diloco_cast_f32_to_bf16.argtypes = [vp, vp, u64, vp]
         L.diloco_set_tuning.argtypes = [vp, C.c_char_p, C.c_int]
         L.diloco_last_error.argtypes = [vp]
         L.diloco_last_error.restype = C.c_char_p
@@ -87,11 +88,11 @@ def _check(rc, ctx=None):
 
 def make_config(numel, k_workers, h_inner_steps=0, inner_lr=4e-4, beta1=0.9, beta2=0.999,
                 eps=1e-8, weight_decay=0.1, outer_lr=0.7, outer_momentum=0.9, pg_dtype=F32,
-                arena=None, arena_bytes=0, stream=None):
+                pg_round_mean=0, arena=None, arena_bytes=0, stream=None):
     arr = (C.c_uint64 * len(numel))(*[int(n) for n in numel])
     cfg = Config(len(numel), C.cast(arr, C.POINTER(C.c_uint64)), k_workers, h_inner_steps,
                  inner_lr, beta1, beta2, eps, weight_decay, outer_lr, outer_momentum, pg_dtype,
-                 arena, arena_bytes, stream)
+                 int(pg_round_mean), arena, arena_bytes, stream)
     cfg._keep = arr
     return cfg
 
@@ -148,6 +149,10 @@ def diloco_get_steps(ctx, k):
 
 def diloco_cast_f32_to_f16(in_ptr, out_ptr, n, stream=None):
     return _check(lib().diloco_cast_f32_to_f16(in_ptr, out_ptr, n, stream))
+
+
+def diloco_cast_f32_to_bf16(in_ptr, out_ptr, n, stream=None):
+    return _check(lib().diloco_cast_f32_to_bf16(in_ptr, out_ptr, n, stream))
 
 
 def diloco_set_tuning(ctx, name, value):

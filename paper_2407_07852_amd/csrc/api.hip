@@ -96,8 +96,10 @@ int validate_hyper(const diloco_config* cfg) {
     return fail(nullptr, DILOCO_ERR_INVALID_ARG, "weight_decay must be finite and >= 0");
   if (!finite_in(cfg->outer_momentum, 0, false, 1, true))
     return fail(nullptr, DILOCO_ERR_INVALID_ARG, "outer_momentum must be in [0, 1)");
-  if (cfg->pg_dtype != DILOCO_F32 && cfg->pg_dtype != DILOCO_F16)
+  if (cfg->pg_dtype != DILOCO_F32 && cfg->pg_dtype != DILOCO_F16 && cfg->pg_dtype != DILOCO_BF16)
     return fail(nullptr, DILOCO_ERR_INVALID_ARG, "unknown pg_dtype %d", cfg->pg_dtype);
+  if (cfg->pg_round_mean != 0 && cfg->pg_round_mean != 1)
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "pg_round_mean must be 0 or 1");
   return DILOCO_OK;
 }
 
@@ -420,7 +422,8 @@ int diloco_outer_step(diloco_ctx* ctx) {
   a.mu = (float)ctx->cfg.outer_momentum;
   a.kf = (float)ctx->cfg.k_workers;
   a.k = (int)ctx->cfg.k_workers;
-  a.f16 = ctx->cfg.pg_dtype == DILOCO_F16;
+  a.pg = ctx->cfg.pg_dtype;
+  a.round_mean = ctx->cfg.pg_round_mean;
   hipError_t e = launch_outer(a, ctx->tune, ctx->n_cu, ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, "outer step launch", e);
   ctx->steps_since_outer = 0;
@@ -463,14 +466,24 @@ int diloco_get_steps(diloco_ctx* ctx, uint32_t* steps) {
   return DILOCO_OK;
 }
 
+static int cast_common(const float* in, uint16_t* out, uint64_t n, int pg, void* stream);
+
 int diloco_cast_f32_to_f16(const float* in, uint16_t* out, uint64_t n, void* stream) {
+  return cast_common(in, out, n, DILOCO_F16, stream);
+}
+
+int diloco_cast_f32_to_bf16(const float* in, uint16_t* out, uint64_t n, void* stream) {
+  return cast_common(in, out, n, DILOCO_BF16, stream);
+}
+
+static int cast_common(const float* in, uint16_t* out, uint64_t n, int pg, void* stream) {
   if (n == 0) return DILOCO_OK;
   if (!in || !out) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "NULL argument");
   int rc = check_device_range(nullptr, in, n * 4, "in");
   if (rc != DILOCO_OK) return rc;
   rc = check_device_range(nullptr, out, n * 2, "out");
   if (rc != DILOCO_OK) return rc;
-  hipError_t e = launch_cast(in, out, n, (hipStream_t)stream);
+  hipError_t e = launch_cast(in, out, n, pg, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(nullptr, "cast launch", e);
   return DILOCO_OK;
 }
@@ -480,13 +493,10 @@ int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value) {
   Tuning& t = ctx->tune;
   const std::string n(name);
   if (n == "inner_vec" && (value == 1 || value == 2 || value == 4)) t.inner_vec = value;
-  else if (n == "outer_vec" && (value == 1 || value == 2)) t.outer_vec = value;
   else if (n == "inner_block" && (value == 64 || value == 128 || value == 256)) t.inner_block = value;
-  else if (n == "outer_block" && (value == 64 || value == 256)) t.outer_block = value;
   else if (n == "inner_waves" && value >= -1 && value <= 32) t.inner_waves = value;
   else if (n == "outer_waves" && value >= -1 && value <= 32) t.outer_waves = value;
   else if (n == "inner_nt" && (value == 0 || value == 1)) t.inner_nt = value;
-  else if (n == "outer_nt" && (value == 0 || value == 1)) t.outer_nt = value;
   else if (n == "check_block" && (value == 64 || value == 256)) t.check_block = value;
   else if (n == "check_vec" && (value == 1 || value == 2 || value == 4 || value == 8)) t.check_vec = value;
   else if (n == "check_waves" && value >= 0 && value <= 32) t.check_waves = value;

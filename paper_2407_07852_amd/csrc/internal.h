@@ -20,16 +20,13 @@ struct Tuning {
   int inner_vec = 1;      // 128-bit vectors per thread per stream (1, 2, 4)
   int inner_nt = 1;       // nontemporal loads/stores
   int inner_waves = -1;   // resident waves per CU: -1 = auto, 0 = hardware maximum
-  int outer_block = 64;   // 64 or 256
-  int outer_vec = 1;      // 1 or 2
-  int outer_nt = 1;
-  int outer_waves = -1;
+  int outer_waves = -1;   // resident waves per CU for the outer step: -1 = auto, 0 = maximum
   int check_block = 256;  // 64 or 256
   int check_vec = 4;      // 1, 2, 4 (8 with 64-thread blocks)
   int check_waves = 16;   // resident waves per CU (0 = hardware maximum)
   int check_persist = 0;  // inf/NaN check: grid-stride blocks per CU (0: one tile per block)
   uint32_t lds_per_cu = 160 * 1024;  // set from the device properties at init
-  int xcd_remap = 0;      // 1: give each of the 8 XCDs a contiguous range of tiles
+  int xcd_remap = 0;  // inner step only;      // 1: give each of the 8 XCDs a contiguous range of tiles
 };
 
 struct InnerArgs {
@@ -59,7 +56,8 @@ struct OuterArgs {
   uint64_t n_pad;
   float lr, mu, kf;
   int k;
-  int f16;
+  int pg;          // pseudo-gradient type: 0 binary32, 1 binary16, 2 bfloat16
+  int round_mean;  // also round the average through that type
 };
 
 hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const Tuning& t,
@@ -69,6 +67,6 @@ hipError_t launch_check(const void* g, uint64_t g_stride, uint64_t n_pad, int k,
                         int32_t* found_inf, const Tuning& t, int n_cu, hipStream_t s);
 hipError_t launch_init_state(float* theta0, float* mom, float* theta, float* m, float* v,
                              uint64_t stride, uint64_t n_pad, int k, hipStream_t s);
-hipError_t launch_cast(const float* in, uint16_t* out, uint64_t n, hipStream_t s);
+hipError_t launch_cast(const float* in, uint16_t* out, uint64_t n, int pg, hipStream_t s);
 
 }  // namespace diloco

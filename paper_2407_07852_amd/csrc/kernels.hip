@@ -171,11 +171,18 @@ __global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32
 // workers, Nesterov SGD on theta0, and the reset of every worker to the new theta0.
 // The pseudo-gradients never leave registers.
 // ------------------------------------------------------------------------------------------
-template <bool F16>
+// Rounds x through the pseudo-gradient type PG (0 binary32, 1 binary16, 2 bfloat16) with the
+// hardware's round-to-nearest-even conversions (subnormals kept) and widens it back.
+template <int PG>
+__device__ __forceinline__ float round_through(float x) {
+  if constexpr (PG == 1) x = (float)(_Float16)x;  // v_cvt_f16_f32 and back
+  if constexpr (PG == 2) x = (float)(__bf16)x;    // v_cvt_pk_bf16_f32 and back
+  return x;
+}
+
+template <int PG>
 __device__ __forceinline__ float pseudo_grad(float th0, float th_r) {
-  float d = th0 - th_r;
-  if constexpr (F16) d = (float)(_Float16)d;  // v_cvt_f16_f32 (RNE, subnormals kept) and back
-  return d;
+  return round_through<PG>(th0 - th_r);
 }
 
 __device__ __forceinline__ void nesterov_elem(float& th0, float& b, float dbar, float lr,
@@ -185,54 +192,45 @@ __device__ __forceinline__ void nesterov_elem(float& th0, float& b, float dbar, 
   b = bn;
 }
 
-template <int B, int K, int V, bool F16, bool NT, bool REMAP>
-__global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint32_t tiles) {
-  const uint32_t tile = tile_of_block(REMAP);
-  if constexpr (REMAP) {
-    if (tile >= tiles) return;
-  }
+// One single-wave workgroup per 256-element tile: all K+2 loads in flight, then the arithmetic,
+// then K+2 stores.  RM: the average is rounded through the pseudo-gradient type as well.
+template <int K, int PG, bool RM>
+__global__ __launch_bounds__(64) void outer_fused_kernel(const OuterArgs a, uint32_t tiles) {
+  constexpr bool NT = true;
+  const uint32_t tile = blockIdx.x;  // the grid holds exactly one workgroup per tile
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
   const size_t rstride = a.stride / kVecElems;  // replica stride in vectors
-  const size_t base = (size_t)tile * (B * V) + threadIdx.x;
-  f32x4 t0[V], b[V], th[K][V];
+  const size_t i = (size_t)tile * 64 + threadIdx.x;
+  f32x4 t0 = ld<NT>(t0_p + i);
+  f32x4 b = ld<NT>(b_p + i);
+  f32x4 th[K];
 #pragma unroll
-  for (int j = 0; j < V; ++j) {
-    const size_t i = base + (size_t)j * B;
-    t0[j] = ld<NT>(t0_p + i);
-    b[j] = ld<NT>(b_p + i);
+  for (int r = 0; r < K; ++r) th[r] = ld<NT>(th_p + (size_t)r * rstride + i);
 #pragma unroll
-    for (int r = 0; r < K; ++r) th[r][j] = ld<NT>(th_p + (size_t)r * rstride + i);
+  for (int c = 0; c < kVecElems; ++c) {
+    float s = pseudo_grad<PG>(t0[c], th[0][c]);
+#pragma unroll
+    for (int r = 1; r < K; ++r) s = s + pseudo_grad<PG>(t0[c], th[r][c]);
+    float dbar = s / a.kf;
+    if constexpr (RM) dbar = round_through<PG>(dbar);
+    float t = t0[c], bb = b[c];
+    nesterov_elem(t, bb, dbar, a.lr, a.mu);
+    t0[c] = t;
+    b[c] = bb;
   }
+  st<NT>(t0_p + i, t0);
+  st<NT>(b_p + i, b);
 #pragma unroll
-  for (int j = 0; j < V; ++j) {
-#pragma unroll
-    for (int c = 0; c < kVecElems; ++c) {
-      float s = pseudo_grad<F16>(t0[j][c], th[0][j][c]);
-#pragma unroll
-      for (int r = 1; r < K; ++r) s = s + pseudo_grad<F16>(t0[j][c], th[r][j][c]);
-      const float dbar = s / a.kf;
-      float t = t0[j][c], bb = b[j][c];
-      nesterov_elem(t, bb, dbar, a.lr, a.mu);
-      t0[j][c] = t;
-      b[j][c] = bb;
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < V; ++j) {
-    const size_t i = base + (size_t)j * B;
-    st<NT>(t0_p + i, t0[j]);
-    st<NT>(b_p + i, b[j]);
-#pragma unroll
-    for (int r = 0; r < K; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0[j]);
-  }
+  for (int r = 0; r < K; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0);
   if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
 // Any k (run-time loop over the workers): one single-wave workgroup per 256-element tile.
-template <bool F16, bool NT>
+template <int PG, bool RM>
 __global__ __launch_bounds__(64) void outer_fused_anyk_kernel(const OuterArgs a, uint32_t tiles) {
+  constexpr bool NT = true;
   const uint32_t tile = blockIdx.x;  // the grid holds exactly one workgroup per tile
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
@@ -245,17 +243,18 @@ __global__ __launch_bounds__(64) void outer_fused_anyk_kernel(const OuterArgs a,
   {
     const f32x4 th = ld<NT>(th_p + i);
 #pragma unroll
-    for (int c = 0; c < kVecElems; ++c) s[c] = pseudo_grad<F16>(t0[c], th[c]);
+    for (int c = 0; c < kVecElems; ++c) s[c] = pseudo_grad<PG>(t0[c], th[c]);
   }
 #pragma unroll 4
   for (int r = 1; r < a.k; ++r) {
     const f32x4 th = ld<NT>(th_p + (size_t)r * rstride + i);
 #pragma unroll
-    for (int c = 0; c < kVecElems; ++c) s[c] = s[c] + pseudo_grad<F16>(t0[c], th[c]);
+    for (int c = 0; c < kVecElems; ++c) s[c] = s[c] + pseudo_grad<PG>(t0[c], th[c]);
   }
 #pragma unroll
   for (int c = 0; c < kVecElems; ++c) {
-    const float dbar = s[c] / a.kf;
+    float dbar = s[c] / a.kf;
+    if constexpr (RM) dbar = round_through<PG>(dbar);
     float t = t0[c], bb = b[c];
     nesterov_elem(t, bb, dbar, a.lr, a.mu);
     t0[c] = t;
@@ -345,14 +344,19 @@ __global__ __launch_bounds__(kBlock) void init_state_kernel(const float* theta0,
   }
 }
 
-__global__ __launch_bounds__(kBlock) void cast_f16_kernel(const float* __restrict__ in,
-                                                          uint16_t* __restrict__ out,
-                                                          uint64_t n) {
+template <int PG>
+__global__ __launch_bounds__(kBlock) void cast_kernel(const float* __restrict__ in,
+                                                      uint16_t* __restrict__ out, uint64_t n) {
   const size_t step = (size_t)gridDim.x * kBlock;
   for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += step) {
-    const _Float16 h = (_Float16)in[i];
     uint16_t bits;
-    __builtin_memcpy(&bits, &h, 2);
+    if constexpr (PG == 1) {
+      const _Float16 h = (_Float16)in[i];
+      __builtin_memcpy(&bits, &h, 2);
+    } else {
+      const __bf16 h = (__bf16)in[i];
+      __builtin_memcpy(&bits, &h, 2);
+    }
     out[i] = bits;
   }
 }
@@ -446,45 +450,31 @@ hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const 
              : launch_inner_n<false, false>(a, k, t, n_cu, s);
 }
 
-template <int B, int K, int V, bool F16, bool NT>
-static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
-  const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
-  const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0));
+template <int K, int PG, bool RM>
+static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
+  const uint64_t tiles = a.n_pad / (uint64_t)(64 * kVecElems);
   const uint32_t lds = pad_lds_bytes(
-      t.outer_waves < 0 ? auto_waves((K + 2) * 1024 * V) : t.outer_waves, B, t.lds_per_cu);
-  if (t.xcd_remap)
-    hipLaunchKernelGGL((outer_fused_kernel<B, K, V, F16, NT, true>), grid, dim3(B), lds, s, a,
-                       (uint32_t)tiles);
-  else
-    hipLaunchKernelGGL((outer_fused_kernel<B, K, V, F16, NT, false>), grid, dim3(B), lds, s, a,
-                       (uint32_t)tiles);
+      t.outer_waves < 0 ? auto_waves((K + 2) * 1024) : t.outer_waves, 64, t.lds_per_cu);
+  hipLaunchKernelGGL((outer_fused_kernel<K, PG, RM>), dim3((uint32_t)tiles), dim3(64), lds, s, a,
+                     (uint32_t)tiles);
   return hipGetLastError();
 }
 
-template <int K, bool F16, bool NT>
-static hipError_t launch_outer_v(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
-  if (t.outer_block == 256)
-    return t.outer_vec == 2 ? launch_outer_t<256, K, 2, F16, NT>(a, t, n_cu, s)
-                            : launch_outer_t<256, K, 1, F16, NT>(a, t, n_cu, s);
-  return t.outer_vec == 2 ? launch_outer_t<64, K, 2, F16, NT>(a, t, n_cu, s)
-                          : launch_outer_t<64, K, 1, F16, NT>(a, t, n_cu, s);
-}
-
-template <bool F16, bool NT>
-static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
+template <int PG, bool RM>
+static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, hipStream_t s) {
   switch (a.k) {
-    case 1: return launch_outer_v<1, F16, NT>(a, t, n_cu, s);
-    case 2: return launch_outer_v<2, F16, NT>(a, t, n_cu, s);
-    case 3: return launch_outer_v<3, F16, NT>(a, t, n_cu, s);
-    case 4: return launch_outer_v<4, F16, NT>(a, t, n_cu, s);
-    case 5: return launch_outer_v<5, F16, NT>(a, t, n_cu, s);
-    case 6: return launch_outer_v<6, F16, NT>(a, t, n_cu, s);
-    case 7: return launch_outer_v<7, F16, NT>(a, t, n_cu, s);
-    case 8: return launch_outer_v<8, F16, NT>(a, t, n_cu, s);
+    case 1: return launch_outer_t<1, PG, RM>(a, t, s);
+    case 2: return launch_outer_t<2, PG, RM>(a, t, s);
+    case 3: return launch_outer_t<3, PG, RM>(a, t, s);
+    case 4: return launch_outer_t<4, PG, RM>(a, t, s);
+    case 5: return launch_outer_t<5, PG, RM>(a, t, s);
+    case 6: return launch_outer_t<6, PG, RM>(a, t, s);
+    case 7: return launch_outer_t<7, PG, RM>(a, t, s);
+    case 8: return launch_outer_t<8, PG, RM>(a, t, s);
     default: {
       const uint64_t tiles = a.n_pad / (uint64_t)(64 * kVecElems);
       const int waves = t.outer_waves < 0 ? auto_waves((a.k + 2) * 1024) : t.outer_waves;
-      hipLaunchKernelGGL((outer_fused_anyk_kernel<F16, NT>), dim3((uint32_t)tiles), dim3(64),
+      hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM>), dim3((uint32_t)tiles), dim3(64),
                          pad_lds_bytes(waves, 64, t.lds_per_cu), s, a, (uint32_t)tiles);
       return hipGetLastError();
     }
@@ -492,10 +482,13 @@ static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, int n_cu, 
 }
 
 hipError_t launch_outer(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
-  if (a.f16) return t.outer_nt ? launch_outer_k<true, true>(a, t, n_cu, s)
-                               : launch_outer_k<true, false>(a, t, n_cu, s);
-  return t.outer_nt ? launch_outer_k<false, true>(a, t, n_cu, s)
-                    : launch_outer_k<false, false>(a, t, n_cu, s);
+  (void)n_cu;
+  const bool rm = a.round_mean != 0;
+  switch (a.pg) {
+    case 1: return rm ? launch_outer_k<1, true>(a, t, s) : launch_outer_k<1, false>(a, t, s);
+    case 2: return rm ? launch_outer_k<2, true>(a, t, s) : launch_outer_k<2, false>(a, t, s);
+    default: return launch_outer_k<0, false>(a, t, s);  // FP32: rounding the mean is a no-op
+  }
 }
 
 template <int B, int V>
@@ -541,11 +534,14 @@ hipError_t launch_init_state(float* theta0, float* mom, float* theta, float* m, 
   return hipGetLastError();
 }
 
-hipError_t launch_cast(const float* in, uint16_t* out, uint64_t n, hipStream_t s) {
+hipError_t launch_cast(const float* in, uint16_t* out, uint64_t n, int pg, hipStream_t s) {
   uint64_t blocks = (n + kBlock - 1) / kBlock;
   if (blocks > 65536) blocks = 65536;
   if (blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(cast_f16_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, s, in, out, n);
+  if (pg == 2)
+    hipLaunchKernelGGL(cast_kernel<2>, dim3((uint32_t)blocks), dim3(kBlock), 0, s, in, out, n);
+  else
+    hipLaunchKernelGGL(cast_kernel<1>, dim3((uint32_t)blocks), dim3(kBlock), 0, s, in, out, n);
   return hipGetLastError();
 }
 

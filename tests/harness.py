@@ -22,7 +22,9 @@ def oracle_layout(wl):
 class GpuSide:
     """The HIP library on the workload, inputs generated on the device."""
 
-    def __init__(self, wl, k, pg_f16=False, hp=None, h=0):
+    def __init__(self, wl, k, pg_f16=False, hp=None, h=0, round_mean=False):
+        """pg_f16: False (FP32), True (FP16) or an oracle.PG_* code (the library uses the same
+        numbering)."""
         import torch
         import paper_2407_07852_amd as D
         self.torch, self.D, self.wl, self.k = torch, D, wl, k
@@ -37,7 +39,7 @@ class GpuSide:
                                   stream=torch.cuda.current_stream().cuda_stream)
 
         self.dl = D.DiLoCo(wl.numel, k, fill_theta0=fill, h_inner_steps=h,
-                           pg_dtype=D.F16 if pg_f16 else D.F32, **hp)
+                           pg_dtype=oracle._pg_code(pg_f16), pg_round_mean=int(round_mean), **hp)
         self.n_pad = self.dl.layout.n_pad
         self.grads = None
 
@@ -70,7 +72,7 @@ class GpuSide:
 class CpuSide:
     """The oracle on the same workload, inputs generated on the host."""
 
-    def __init__(self, wl, k, pg_f16=False, hp=None):
+    def __init__(self, wl, k, pg_f16=False, hp=None, round_mean=False):
         hp = dict(PAPER_HP if hp is None else hp)
         self.wl, self.k = wl, k
         self.offsets, self.n_pad = oracle_layout(wl)
@@ -79,7 +81,7 @@ class CpuSide:
                                      self.kind, ones_as_one=True)
         self.o = oracle.DiLoCoOracle(theta0, k, hp["inner_lr"], hp["beta1"], hp["beta2"],
                                      hp["eps"], hp["weight_decay"], hp["outer_lr"],
-                                     hp["outer_momentum"], pg_f16)
+                                     hp["outer_momentum"], pg_f16, round_mean)
 
     def set_groups(self, group_of_tensor, lr_scale, weight_decay):
         self.o.groups = oracle.ParamGroups(self.offsets, self.wl.numel, group_of_tensor, lr_scale,
