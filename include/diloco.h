@@ -180,8 +180,13 @@ int diloco_get_steps(diloco_ctx* ctx, uint32_t* steps);
 int diloco_cast_f32_to_f16(const float* in, uint16_t* out, uint64_t n, void* stream);
 int diloco_cast_f32_to_bf16(const float* in, uint16_t* out, uint64_t n, void* stream);
 
-/* Launch-shape knobs for benchmarking sweeps; results never depend on them.  Unknown names
- * return DILOCO_ERR_INVALID_ARG. */
+/* Launch-shape knobs for benchmarking sweeps; results never depend on them.  Names and values:
+ *   inner_block 64|256, inner_vec 1|4 (threads per workgroup, 128-bit vectors per lane and stream),
+ *   inner_nt 0|1 (nontemporal accesses), xcd_remap 0|1 (inner step: contiguous tile range per XCD),
+ *   inner_waves / outer_waves -1..32 (resident waves per CU: -1 automatic, 0 hardware maximum),
+ *   check_block 64|256, check_vec 1|2|4|8, check_waves 0..32, check_persist 0..64.
+ * The defaults are the measured optimum on MI355X.  Unknown names or values return
+ * DILOCO_ERR_INVALID_ARG. */
 int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value);
 
 /* Message of the most recent error on this context (ctx may be NULL: the calling thread's

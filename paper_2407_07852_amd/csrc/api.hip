@@ -492,8 +492,8 @@ int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value) {
   if (!ctx || !name) return fail(ctx, DILOCO_ERR_INVALID_ARG, "NULL argument");
   Tuning& t = ctx->tune;
   const std::string n(name);
-  if (n == "inner_vec" && (value == 1 || value == 2 || value == 4)) t.inner_vec = value;
-  else if (n == "inner_block" && (value == 64 || value == 128 || value == 256)) t.inner_block = value;
+  if (n == "inner_vec" && (value == 1 || value == 4)) t.inner_vec = value;
+  else if (n == "inner_block" && (value == 64 || value == 256)) t.inner_block = value;
   else if (n == "inner_waves" && value >= -1 && value <= 32) t.inner_waves = value;
   else if (n == "outer_waves" && value >= -1 && value <= 32) t.outer_waves = value;
   else if (n == "inner_nt" && (value == 0 || value == 1)) t.inner_nt = value;

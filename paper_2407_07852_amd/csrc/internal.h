@@ -16,8 +16,8 @@ struct RepState {
 
 // Launch-shape knobs (see diloco_set_tuning).
 struct Tuning {
-  int inner_block = 64;   // threads per workgroup (64, 128, 256)
-  int inner_vec = 1;      // 128-bit vectors per thread per stream (1, 2, 4)
+  int inner_block = 64;   // threads per workgroup (64 or 256)
+  int inner_vec = 1;      // 128-bit vectors per thread per stream (1 or 4)
   int inner_nt = 1;       // nontemporal loads/stores
   int inner_waves = -1;   // resident waves per CU: -1 = auto, 0 = hardware maximum
   int outer_waves = -1;   // resident waves per CU for the outer step: -1 = auto, 0 = maximum

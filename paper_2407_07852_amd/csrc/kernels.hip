@@ -1,8 +1,9 @@
 // gfx950 (MI355X, CDNA4) kernels of the DiLoCo optimizer hot path.
 //
 // Everything here is elementwise and HBM-bound, so the design is about memory streams, not
-// arithmetic: flat padded buffers, one 128-bit load/store per lane per access, every buffer
-// streamed exactly once per step, several independent vectors in flight per lane, and
+// arithmetic: flat padded buffers, one 128-bit load/store per lane per stream, every buffer
+// streamed exactly once per step, one 256-element tile per single-wave workgroup handed out in
+// address order by the hardware dispatcher, a capped number of waves resident per CU, and
 // nontemporal accesses because nothing is reused.  No MFMA: there is no contraction.
 //
 // Floating point follows the method's definition operation by operation: IEEE binary32,
@@ -418,21 +419,15 @@ static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int
 template <int B, bool G16, bool NT, bool GROUPS>
 static hipError_t launch_inner_b(const InnerArgs& a, int k, const Tuning& t, int n_cu,
                                  hipStream_t s) {
-  switch (t.inner_vec) {
-    case 2: return launch_inner_t<B, 2, G16, NT, GROUPS>(a, k, t, n_cu, s);
-    case 4: return launch_inner_t<B, 4, G16, NT, GROUPS>(a, k, t, n_cu, s);
-    default: return launch_inner_t<B, 1, G16, NT, GROUPS>(a, k, t, n_cu, s);
-  }
+  if (t.inner_vec == 4) return launch_inner_t<B, 4, G16, NT, GROUPS>(a, k, t, n_cu, s);
+  return launch_inner_t<B, 1, G16, NT, GROUPS>(a, k, t, n_cu, s);
 }
 
 template <bool G16, bool NT, bool GROUPS>
 static hipError_t launch_inner_v(const InnerArgs& a, int k, const Tuning& t, int n_cu,
                                  hipStream_t s) {
-  switch (t.inner_block) {
-    case 128: return launch_inner_b<128, G16, NT, GROUPS>(a, k, t, n_cu, s);
-    case 256: return launch_inner_b<256, G16, NT, GROUPS>(a, k, t, n_cu, s);
-    default: return launch_inner_b<64, G16, NT, GROUPS>(a, k, t, n_cu, s);
-  }
+  if (t.inner_block == 256) return launch_inner_b<256, G16, NT, GROUPS>(a, k, t, n_cu, s);
+  return launch_inner_b<64, G16, NT, GROUPS>(a, k, t, n_cu, s);
 }
 
 template <bool G16, bool GROUPS>

@@ -71,7 +71,8 @@ def test_reduced_precision_pseudo_gradient_modes(k, pg, round_mean):
 
 
 @pytest.mark.parametrize("tune", [dict(inner_block=256, inner_vec=4),
-                                  dict(inner_block=128, inner_vec=2, xcd_remap=1),
+                                  dict(inner_block=256, inner_vec=1, xcd_remap=1),
+                                  dict(inner_block=64, inner_vec=4, xcd_remap=1),
                                   dict(inner_nt=0),
                                   dict(inner_waves=0, outer_waves=0, check_waves=0),
                                   dict(inner_waves=3, outer_waves=16, check_block=64, check_vec=8,
@@ -187,7 +188,8 @@ def test_error_paths():
                                                flags.data_ptr())) == D.ERR_INVALID_ARG
     assert code(lambda: D.diloco_get_buffer(dl.ctx, D.BUF_THETA, 2)) == D.ERR_INVALID_ARG
     assert code(lambda: D.diloco_set_tuning(dl.ctx, "inner_vec", 3)) == D.ERR_INVALID_ARG
-    assert "inner_vec" in D.diloco_last_error(dl.ctx)
+    assert code(lambda: D.diloco_set_tuning(dl.ctx, "no_such_knob", 1)) == D.ERR_INVALID_ARG
+    assert "no_such_knob" in D.diloco_last_error(dl.ctx)
     # nothing was launched by any failed call
     assert dl.steps() == [0, 0]
     # arena too small / misaligned
