@@ -73,7 +73,7 @@ enum { /* diloco_get_buffer selector */
  * 0.9; betas and eps are not printed by the paper), H, k and the pseudo-gradient type. */
 typedef struct {
   uint32_t n_tensors;       /* >= 1 */
-  const uint64_t* numel;    /* host array [n_tensors], each >= 1; copied at init */
+  const uint64_t* numel;    /* host array [n_tensors], each >= 1, sum <= 2^33; copied at init */
   uint32_t k_workers;       /* 1 .. DILOCO_MAX_WORKERS */
   uint32_t h_inner_steps;   /* H; only used to report DILOCO_ROUND_COMPLETE; 0 = never */
   double inner_lr;          /* AdamW: >= 0, finite */
@@ -89,7 +89,9 @@ typedef struct {
   int32_t pg_round_mean;    /* 0: the average stays FP32 (default).  1: the average is rounded
                                through pg_dtype as well, as the output of an all-reduce whose
                                buffer has that type would be (no effect with DILOCO_F32) */
-  void* arena;              /* device, caller-owned, 256-byte aligned; unused by query_layout */
+  void* arena;              /* device, caller-owned, 256-byte aligned (2 MiB alignment, which large
+                               allocations have anyway, is what the layout's stride assumes for
+                               best bandwidth); unused by query_layout */
   uint64_t arena_bytes;
   void* stream;             /* hipStream_t, borrowed; NULL = the default stream */
 } diloco_config;

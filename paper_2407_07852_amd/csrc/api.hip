@@ -77,8 +77,10 @@ int validate_problem(const diloco_config* cfg) {
   for (uint32_t t = 0; t < cfg->n_tensors; ++t) {
     if (cfg->numel[t] == 0)
       return fail(nullptr, DILOCO_ERR_INVALID_ARG, "tensor %u has zero elements", t);
-    if (cfg->numel[t] > (1ull << 40) || (total += cfg->numel[t]) > (1ull << 40))
-      return fail(nullptr, DILOCO_ERR_INVALID_ARG, "parameter count exceeds 2^40");
+    // 2^33 elements per replica keeps (workgroups x 64 threads) of the one-tile-per-workgroup
+    // launches below 2^32; five FP32 buffers of that size already exceed the GPU's memory.
+    if (cfg->numel[t] > (1ull << 33) || (total += cfg->numel[t]) > (1ull << 33))
+      return fail(nullptr, DILOCO_ERR_INVALID_ARG, "parameter count exceeds 2^33 per replica");
   }
   return DILOCO_OK;
 }

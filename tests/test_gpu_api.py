@@ -15,7 +15,7 @@ def _ragged(n):
                                            for j, s in enumerate(synth.ragged_sizes(n))])
 
 
-@pytest.mark.parametrize("k", [1, 3, 5, 8, 9, 16])
+@pytest.mark.parametrize("k", [1, 3, 5, 8, 9, 16, 33, 64])
 @pytest.mark.parametrize("pg_f16", [False, True])
 def test_round_for_various_k(k, pg_f16):
     wl = _ragged(40)

@@ -83,6 +83,9 @@ def test_bad_problems_are_rejected_on_the_host():
     assert code(D.make_config([], 2)) == D.ERR_INVALID_ARG
     assert code(D.make_config([4, 0, 3], 2)) == D.ERR_INVALID_ARG
     assert code(D.make_config([4], 0)) == D.ERR_INVALID_ARG
+    assert code(D.make_config([1 << 33, 1], 1)) == D.ERR_INVALID_ARG
+    lay, _ = D.diloco_query_layout(D.make_config([1 << 33], 1))      # the largest accepted size
+    assert lay.n_pad == 1 << 33
     assert code(D.make_config([4], D.MAX_WORKERS + 1)) == D.ERR_INVALID_ARG
     assert "k_workers" in D.diloco_last_error()
     for bad in (dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0), dict(inner_lr=-1.0),
@@ -145,3 +148,47 @@ def test_lr_schedule_matches_oracle():
                                                                                   4e-4, ratio)
     assert np.isnan(D.diloco_lr_at(1, 10, 0, -1.0, 1.0))
     assert np.isnan(D.diloco_lr_at(1, 10, 0, float("inf"), 1.0))
+
+
+def test_workload_shapes_follow_the_papers_model_table():
+    """Layers / hidden size / vocabulary of the synthetic tensor lists are the ones the paper's
+    model-configuration table prints (tests/golden/model_shapes.txt)."""
+    rows = {}
+    with open(os.path.join(ROOT, "tests", "golden", "model_shapes.txt")) as f:
+        for line in f:
+            line = line.split("#", 1)[0].split()
+            if len(line) == 6:
+                rows[line[0]] = [int(x) for x in line[1:]]
+    for name, wl in (("llama_150m", synth.llama_150m()), ("llama_1_1b", synth.llama_1_1b())):
+        layers, hidden, heads, kv_size, vocab = rows[name]
+        norms = [s for s in wl.shapes if len(s) == 1]
+        assert len(norms) == 2 * layers and all(s == (hidden,) for s in norms)
+        assert wl.shapes[-1] == (vocab, hidden)
+        square = [s for s in wl.shapes if s == (hidden, hidden)]
+        assert len(square) >= 2 * layers                   # q and o projections
+        assert hidden == heads * kv_size                   # head size as printed
+        kv = [s for s in wl.shapes if len(s) == 2 and s[1] == hidden and s[0] % kv_size == 0]
+        assert kv
+
+
+def test_product_sources_never_reach_into_the_oracle():
+    """The HIP path and its binding share nothing with the oracle: no import, include or path."""
+    pkg = os.path.join(ROOT, "paper_2407_07852_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, fn)
+    for fn in ("diloco_oracle.cpp", "__init__.py", "build.py"):
+        text = open(os.path.join(ROOT, "oracle", fn)).read()
+        assert "paper_2407_07852_amd" not in text and "csrc" not in text and "hip/" not in text
+    header = open(os.path.join(ROOT, "include", "diloco.h")).read()
+    assert "oracle" not in header.lower()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "single-GPU" in (r.stderr + r.stdout)
