@@ -10,7 +10,7 @@ PAPER_HP = dict(inner_lr=4e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.
                 outer_lr=0.7, outer_momentum=0.9)
 W_SIGMA, G_SIGMA = 0.02, 1e-3
 
-# spec tolerances
+# tolerances of the contract: per step 1e-6 relative / 1e-7 absolute, 1e-5 relative after a round
 STEP_RTOL, STEP_ATOL = 1e-6, 1e-7
 ROUND_RTOL = 1e-5
 
