@@ -37,7 +37,7 @@ def test_150m_k8_short_round_full_arrays():
     gpu.dl.close()
 
 
-def _sampled_round(wl, k, pg_f16, H):
+def _sampled_round(wl, k, pg_f16, H, rounds=1):
     gpu = GpuSide(wl, k, pg_f16, h=H)
     idx = sample_indices(wl, np.asarray(gpu.dl.offsets, dtype=np.uint64), gpu.n_pad)
     cpu = SampledCpuSide(wl, k, idx, pg_f16)
@@ -45,11 +45,23 @@ def _sampled_round(wl, k, pg_f16, H):
     torch = gpu.torch
     idx_dev = torch.from_numpy(idx.astype(np.int64)).to("cuda")
     assert compare("theta0 init", gather_gpu(gpu, gpu.dl.theta0, idx_dev), cpu.o.theta0, 0, 0) == 0
-    for step in range(H):
+    for rnd in range(rounds - 1):
+        # earlier rounds: compared after their outer step only
+        for step in range(rnd * H, (rnd + 1) * H):
+            gpu.dl.inner_step(gpu.gen_grads(step))
+            cpu.o.inner_step(cpu.gen_grads(step))
+        gpu.dl.outer_step()
+        cpu.o.outer_step()
+        assert compare("theta0 r%d" % rnd, gather_gpu(gpu, gpu.dl.theta0, idx_dev), cpu.o.theta0,
+                       0, 0) == 0
+        assert compare("mom r%d" % rnd, gather_gpu(gpu, gpu.dl.mom, idx_dev), cpu.o.b, 0, 0) == 0
+    first = (rounds - 1) * H
+    for step in range(first, first + H):
         g = gpu.gen_grads(step)
         rc = gpu.dl.inner_step(g)
-        assert rc == (1 if step == H - 1 else 0)
+        assert rc == (1 if step == first + H - 1 else 0)
         cpu.o.inner_step(cpu.gen_grads(step))
+        step -= first
         if step in (0, H // 2, H - 1):
             th, m, v = (gather_gpu(gpu, t, idx_dev) for t in (gpu.dl.theta, gpu.dl.m, gpu.dl.v))
             mism = 0
@@ -61,7 +73,7 @@ def _sampled_round(wl, k, pg_f16, H):
             assert mism == 0, "after inner step %d: %d sampled last-bit mismatches" % (step, mism)
             print("%s k=%d inner step %d: %d samples bitwise equal" % (wl.name, k, step, idx.size),
                   flush=True)
-    assert gpu.dl.steps() == [H] * k
+    assert gpu.dl.steps() == [H * rounds] * k
     gpu.dl.outer_step()
     cpu.o.outer_step()
     assert compare("theta0", gather_gpu(gpu, gpu.dl.theta0, idx_dev), cpu.o.theta0, ROUND_RTOL,
@@ -86,6 +98,19 @@ def test_150m_k8_h500_round_sampled(pg_f16):
 @pytest.mark.timeout(1500)
 def test_1_1b_k8_h500_round_sampled_fp16():
     _sampled_round(synth.llama_1_1b(), 8, True, 500)
+
+
+@pytest.mark.timeout(900)
+def test_1_1b_k4_h125_round_sampled_fp16():
+    """The 1.1B configuration as the paper ran it: 4 workers, 125 local steps."""
+    _sampled_round(synth.llama_1_1b(), 4, True, 125)
+
+
+@pytest.mark.timeout(900)
+def test_150m_k4_h50_three_rounds_sampled():
+    """The paper's worker-count ablation setting (H = 50), three consecutive rounds so that the
+    outer momentum and the persistent AdamW moments both matter."""
+    _sampled_round(synth.llama_150m(), 4, True, 50, rounds=3)
 
 
 @pytest.mark.timeout(900)
