@@ -364,12 +364,19 @@ __global__ __launch_bounds__(kBlock) void cast_kernel(const float* __restrict__ 
 
 // Dynamic LDS bytes per workgroup so that at most `waves_per_cu` waves of B-thread workgroups
 // are resident on a CU with `lds_per_cu` bytes of LDS (0 = no cap).
-// Automatic residency: about 44 KiB of loads in flight per CU (measured optimum on MI355X for
-// both steps: 11 waves x 4 KiB for the inner step, 4 waves x 10 KiB for the outer step at k=8).
-int auto_waves(int load_bytes_per_wave) {
-  int w = (44 * 1024 + load_bytes_per_wave / 2) / load_bytes_per_wave;
+// Automatic residency from the bytes of loads one wave has in flight.  Measured optima on
+// MI355X: the inner step wants about 44 KiB of loads in flight per CU (11 waves x 4 KiB), the
+// outer step about 40 KiB for every k (k=1: 14 waves x 3 KiB, k=2: 10 x 4, k=4: 6 x 6,
+// k=8: 4 x 10); one wave more or less costs 1-3 %.
+int auto_waves(int load_bytes_per_wave, int target_bytes_per_cu, bool round_to_nearest) {
+  const int w = (target_bytes_per_cu + (round_to_nearest ? load_bytes_per_wave / 2 : 0)) /
+                load_bytes_per_wave;
   return w < 2 ? 2 : (w > 16 ? 16 : w);
 }
+int auto_waves_inner(int load_bytes_per_wave) {
+  return auto_waves(load_bytes_per_wave, 44 * 1024, true);
+}
+int auto_waves_outer(int k) { return auto_waves((k + 2) * 1024, 40 * 1024, false); }
 
 uint32_t pad_lds_bytes(int waves_per_cu, int block, uint32_t lds_per_cu) {
   if (waves_per_cu <= 0) return 0;
@@ -404,7 +411,7 @@ static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
   const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0), (uint32_t)k);
   // The grouped variant's tile waits for one more dependent scalar load: 3 more waves.
-  const int waves = t.inner_waves < 0 ? auto_waves((G16 ? 3584 : 4096) * V) + (GROUPS ? 3 : 0)
+  const int waves = t.inner_waves < 0 ? auto_waves_inner((G16 ? 3584 : 4096) * V) + (GROUPS ? 3 : 0)
                                       : t.inner_waves;
   const uint32_t lds = pad_lds_bytes(waves, B, t.lds_per_cu);
   if (t.xcd_remap)
@@ -449,7 +456,7 @@ template <int K, int PG, bool RM>
 static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(64 * kVecElems);
   const uint32_t lds = pad_lds_bytes(
-      t.outer_waves < 0 ? auto_waves((K + 2) * 1024) : t.outer_waves, 64, t.lds_per_cu);
+      t.outer_waves < 0 ? auto_waves_outer(K) : t.outer_waves, 64, t.lds_per_cu);
   hipLaunchKernelGGL((outer_fused_kernel<K, PG, RM>), dim3((uint32_t)tiles), dim3(64), lds, s, a,
                      (uint32_t)tiles);
   return hipGetLastError();
@@ -468,7 +475,7 @@ static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, hipStream_
     case 8: return launch_outer_t<8, PG, RM>(a, t, s);
     default: {
       const uint64_t tiles = a.n_pad / (uint64_t)(64 * kVecElems);
-      const int waves = t.outer_waves < 0 ? auto_waves((a.k + 2) * 1024) : t.outer_waves;
+      const int waves = t.outer_waves < 0 ? auto_waves_outer(a.k) : t.outer_waves;
       hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM>), dim3((uint32_t)tiles), dim3(64),
                          pad_lds_bytes(waves, 64, t.lds_per_cu), s, a, (uint32_t)tiles);
       return hipGetLastError();
