@@ -154,11 +154,16 @@ def run_mixed_precision(k, reps, torch, D, synth):
     wl = synth.WORKLOADS["stress"]()
     n = wl.n_params
     stream = torch.cuda.current_stream()
-    dl = D.DiLoCo(wl.numel, k, fill_theta0=lambda t, lay, off: t.normal_(0, 0.02))
-    kind = torch.from_numpy(wl.kind_map(dl.offsets, dl.layout.n_pad)).cuda()
-    dl.theta0.mul_(kind != 0)
-    D.diloco_destroy(dl.ctx)                      # re-initialise with clean pads
-    dl.ctx = D.diloco_init(dl.cfg)
+    holder = {}
+
+    def fill(theta0, layout, offsets):
+        holder["kind"] = torch.from_numpy(wl.kind_map(offsets, layout.n_pad)).to(theta0.device)
+        synth.device_fill_f32(theta0.data_ptr(), layout.n_pad, synth.key(synth.STREAM_WEIGHTS),
+                              0.02, holder["kind"].data_ptr(), ones_as_one=True,
+                              stream=stream.cuda_stream)
+
+    dl = D.DiLoCo(wl.numel, k, fill_theta0=fill)
+    kind = holder["kind"]
     g = dl.new_grads(torch.float16)
     for r in range(k):
         synth.device_fill_f16(g[r].data_ptr(), dl.layout.n_pad, synth.key(synth.STREAM_GRADS, r, 0),

@@ -116,8 +116,8 @@ void plan(const diloco_config* cfg, diloco_layout* lay, uint64_t* offsets) {
   const uint64_t k = cfg->k_workers;
   lay->n_pad = n_pad;
   // All flat buffers start 2 MiB-aligned relative to each other: the k+2 streams of a tile then
-  // share their offset inside the GPU's 2 MiB page fragments (measured +4 % on the outer step; larger alignments and skews
-  // between the buffers measured neutral or worse).
+  // share their offset inside the GPU's 2 MiB page fragments (measured +4 % on the outer step;
+  // larger alignments and skews between the buffers measured neutral or worse).
   lay->stride = round_up(n_pad, DILOCO_STRIDE_ALIGN_BYTES / 4);
   lay->off_theta0 = 0;
   lay->off_mom = lay->stride * 4;
