@@ -133,7 +133,10 @@ int diloco_unscale_check(diloco_ctx* ctx, const void* grads, uint64_t grad_strid
  * found_inf: NULL, or the device flags written by the preceding diloco_unscale_check (else
  * DILOCO_ERR_STATE); a worker whose flag is set skips the step: its weights, moments and step
  * count stay untouched.  Returns DILOCO_ROUND_COMPLETE on every H-th call since the last outer
- * step. */
+ * step.
+ * Stream capture: the call enqueues exactly one kernel and no memset; the per-worker step state
+ * alternates between two device slots from call to call, so a captured HIP graph must hold an
+ * even number of inner steps to be replayable. */
 int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
                       int32_t grad_dtype, double lr, const int32_t* found_inf);
 
@@ -172,6 +175,7 @@ int diloco_outer_step(diloco_ctx* ctx);
 /* Device address of a flat buffer (replica ignored for THETA0 / MOM). */
 int diloco_get_buffer(diloco_ctx* ctx, int which, uint32_t replica, void** dev_ptr);
 
+/* The layout this context was created with (same values as diloco_query_layout). */
 int diloco_get_layout(diloco_ctx* ctx, diloco_layout* out);
 
 /* Per-worker AdamW step counts t_r into the host array steps[k].  Synchronises the stream. */
@@ -195,6 +199,8 @@ int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value);
  * last error from diloco_init / diloco_query_layout).  Never NULL. */
 const char* diloco_last_error(diloco_ctx* ctx);
 
+/* Synchronises the stream, frees the library's own device state and the host context.  The
+ * arena and every caller buffer are left untouched.  NULL is accepted. */
 int diloco_destroy(diloco_ctx* ctx);
 
 #ifdef __cplusplus
