@@ -455,8 +455,15 @@ hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const 
 template <int K, int PG, bool RM>
 static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(64 * kVecElems);
-  const uint32_t lds = pad_lds_bytes(
-      t.outer_waves < 0 ? auto_waves_outer(K) : t.outer_waves, 64, t.lds_per_cu);
+  // With only ~4 waves resident (k >= 7) the conversions of the reduced-precision modes lengthen
+  // each wave's compute phase enough to under-fill the memory pipe: two more waves measured
+  // +0.5...0.9 % there (k = 8), and -2 % at smaller k, where more waves are resident anyway.
+  int waves = t.outer_waves;
+  if (waves < 0) {
+    waves = auto_waves_outer(K);
+    if (PG != 0 && waves <= 4) waves += 2;
+  }
+  const uint32_t lds = pad_lds_bytes(waves, 64, t.lds_per_cu);
   hipLaunchKernelGGL((outer_fused_kernel<K, PG, RM>), dim3((uint32_t)tiles), dim3(64), lds, s, a,
                      (uint32_t)tiles);
   return hipGetLastError();
