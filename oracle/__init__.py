@@ -33,6 +33,7 @@ def lib():
                                                     f64, f64, vp, vp]),
             "oracle_lr_at": (f64, [u64, u64, u64, f64, f64]),
             "oracle_unscale_f16": (None, [vp, f32, vp, sz]),
+            "oracle_unscale_f32": (None, [vp, f32, vp, sz]),
             "oracle_found_inf_f16": (i32, [vp, sz]),
             "oracle_found_inf_f32": (i32, [vp, sz]),
             "oracle_pseudo_grad_f32": (None, [vp, vp, vp, sz]),
@@ -181,6 +182,14 @@ def unscale_f16(g16_bits, inv_scale):
     return out
 
 
+def unscale_f32(g, inv_scale):
+    """float32 gradient * inv_scale, as float32."""
+    g = np.ascontiguousarray(g, dtype=np.float32).reshape(-1)
+    out = np.empty(g.size, dtype=np.float32)
+    lib().oracle_unscale_f32(_p(g, np.float32), inv_scale, _p(out, np.float32), out.size)
+    return out
+
+
 def found_inf(g):
     """1 if any element of g (float32 array, or uint16 array of binary16 codes) is inf/NaN."""
     g = np.ascontiguousarray(g).reshape(-1)
@@ -264,7 +273,8 @@ class DiLoCoOracle:
         self.groups = None   # optional ParamGroups
 
     def inner_step(self, grads, found_inf_flags=None, lr=None, inv_scale=None):
-        """grads[r]: float32 array, or uint16 binary16 codes together with inv_scale."""
+        """grads[r]: float32 array, or uint16 binary16 codes; inv_scale (the gradient scaler's
+        unscale factor) is required with binary16 codes and optional with float32."""
         lr0, b1, b2, eps, wd = self.hp
         for r, st in enumerate(self.workers):
             if found_inf_flags is not None and found_inf_flags[r]:
@@ -272,6 +282,8 @@ class DiLoCoOracle:
             g = grads[r]
             if g.dtype == np.uint16:
                 g = unscale_f16(g, inv_scale)
+            elif inv_scale is not None:
+                g = unscale_f32(g, inv_scale)
             if self.groups is not None:
                 adamw_step_groups(st, g, self.groups, lr0 if lr is None else lr, b1, b2, eps)
             else:

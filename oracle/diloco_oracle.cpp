@@ -293,6 +293,13 @@ void oracle_unscale_f16(const uint16_t* g16, float inv_scale, float* g32, size_t
   for (size_t i = 0; i < n; ++i) g32[i] = f16_to_f32(g16[i]) * inv_scale;
 }
 
+// The same for gradients kept in FP32 under a loss scale: the scaler's unscale is
+// one multiply per element whatever type the gradients are stored in.
+void oracle_unscale_f32(const float* g, float inv_scale, float* g32, size_t n) {
+#pragma omp parallel for schedule(static)
+  for (size_t i = 0; i < n; ++i) g32[i] = g[i] * inv_scale;
+}
+
 // found_inf for one worker: 1 if any element is +-inf or NaN, else 0.
 int32_t oracle_found_inf_f16(const uint16_t* g16, size_t n) {
   int32_t found = 0;

@@ -164,6 +164,35 @@ def test_unscale_is_widen_then_multiply():
     assert np.array_equal(got, want)
 
 
+def test_unscale_of_fp32_gradients():
+    """The scaler's unscale also applies to gradients stored in FP32 ("General Implementation
+    Details": the gradient scaler acts in the inner step).  A power-of-two loss scale is exact,
+    so stepping (g * 2^16, inv_scale 2^-16) must equal stepping (g, no scale) bit for bit; a
+    dropped multiply would change every element; hand values pin a non power-of-two factor."""
+    rng = np.random.default_rng(11)
+    n, k = 4099, 2
+    th0 = rng.normal(scale=0.02, size=n).astype(np.float32)
+    plain = oracle.DiLoCoOracle(th0, k, 4e-4, 0.9, 0.999, 1e-8, 0.1, 0.7, 0.9)
+    scaled = oracle.DiLoCoOracle(th0, k, 4e-4, 0.9, 0.999, 1e-8, 0.1, 0.7, 0.9)
+    for _ in range(3):
+        g = [rng.normal(scale=1e-3, size=n).astype(np.float32) for _ in range(k)]
+        plain.inner_step(g)
+        scaled.inner_step([x * np.float32(65536) for x in g], inv_scale=2.0 ** -16)
+    for a_, b_ in zip(plain.workers, scaled.workers):
+        assert np.array_equal(a_.theta, b_.theta) and np.array_equal(a_.m, b_.m)
+        assert np.array_equal(a_.v, b_.v)
+    # without the factor the scaled gradients give a different result (the multiply is live)
+    other = oracle.DiLoCoOracle(th0, k, 4e-4, 0.9, 0.999, 1e-8, 0.1, 0.7, 0.9)
+    other.inner_step([x * np.float32(65536) for x in g])
+    assert not np.array_equal(other.workers[0].m, plain.workers[0].m)
+    # hand values: 3 * (1/3 rounded to float) rounds to exactly 1; 0.75 * 0.5 = 0.375; -2 * 0.25
+    third = float(np.float32(1 / 3))
+    assert oracle.unscale_f32(np.array([3.0], np.float32), third)[0] == np.float32(1.0)
+    got = oracle.unscale_f32(np.array([0.75, -2.0, 0.0], np.float32), 0.5)
+    assert got.tolist() == [0.375, -1.0, 0.0]
+    assert oracle.unscale_f32(np.array([-2.0], np.float32), 0.25)[0] == np.float32(-0.5)
+
+
 def test_skipped_worker_is_untouched():
     rng = np.random.default_rng(9)
     th0 = rng.normal(scale=0.02, size=257).astype(np.float32)
