@@ -21,16 +21,18 @@ struct diloco_ctx {
   hipStream_t stream;
   int device;
   int n_cu;
-  RepState* d_state;               // device, [2][k]
-  int parity;                      // which half of d_state is current
+  RepState* d_state;               // device, [k]: per-worker step state, advanced on the device
+  StepEntry* d_table;              // device, [k]: per-step scratch written by the prologue launch
   uint32_t steps_since_outer;
+  const void* ok_grads;            // last gradient buffer whose extent was validated ...
+  uint64_t ok_grads_bytes;         // ... for at least this many bytes
   bool have_scale;                 // an unscale_check has recorded (flags, inv_scale)
   float inv_scale;
   const int32_t* checked_flags;
   const void* checked_grads;
   // parameter groups
   uint32_t n_groups;               // 0 = single group from cfg
-  uint8_t* d_chunk_group;          // device, [n_pad / 64]
+  uint32_t* d_chunk_group;         // device, [n_pad / 64] group id bytes, read as 32-bit words
   double lr_scale[DILOCO_MAX_GROUPS];
   double group_wd[DILOCO_MAX_GROUPS];
   Tuning tune;
@@ -128,7 +130,9 @@ void plan(const diloco_config* cfg, diloco_layout* lay, uint64_t* offsets) {
 }
 
 // The [ptr, ptr+bytes) range must lie inside one device allocation of the current device.
-int check_device_range(diloco_ctx* ctx, const void* ptr, uint64_t bytes, const char* name) {
+// device >= 0: it must also be memory of that device.
+int check_device_range(diloco_ctx* ctx, int device, const void* ptr, uint64_t bytes,
+                       const char* name) {
   hipPointerAttribute_t attr;
   hipError_t e = hipPointerGetAttributes(&attr, ptr);
   if (e != hipSuccess) {
@@ -138,12 +142,15 @@ int check_device_range(diloco_ctx* ctx, const void* ptr, uint64_t bytes, const c
   }
   if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)
     return fail(ctx, DILOCO_ERR_INVALID_ARG, "%s is not device memory", name);
+  if (device >= 0 && attr.type == hipMemoryTypeDevice && attr.device != device)
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "%s lives on device %d, the context on device %d",
+                name, attr.device, device);
   hipDeviceptr_t base = nullptr;
   size_t size = 0;
   e = hipMemGetAddressRange(&base, &size, const_cast<void*>(ptr));
   if (e != hipSuccess) {
     // Memory the runtime cannot attribute to one allocation (e.g. virtual-memory mappings):
-    // the pointer class was verified above, the extent cannot be.
+    // the pointer class and device were verified above, the extent cannot be.
     (void)hipGetLastError();
     return DILOCO_OK;
   }
@@ -171,7 +178,15 @@ int check_grads(diloco_ctx* ctx, const void* grads, uint64_t grad_stride, int32_
                 "grads must be 16-byte aligned and grad_stride a multiple of 8 elements");
   const uint64_t esz = grad_dtype == DILOCO_F16 ? 2 : 4;
   const uint64_t bytes = ((uint64_t)(ctx->cfg.k_workers - 1) * grad_stride + ctx->lay.n_pad) * esz;
-  return check_device_range(ctx, grads, bytes, "grads");
+  // Steady state: the same buffer as last time needs no runtime query (a training loop passes
+  // one gradient buffer for thousands of steps; the queries cost two driver calls each).
+  if (grads == ctx->ok_grads && bytes <= ctx->ok_grads_bytes) return DILOCO_OK;
+  const int rc = check_device_range(ctx, ctx->device, grads, bytes, "grads");
+  if (rc == DILOCO_OK) {
+    ctx->ok_grads = grads;
+    ctx->ok_grads_bytes = bytes;
+  }
+  return rc;
 }
 
 }  // namespace
@@ -205,8 +220,10 @@ int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco
   plan(&c->cfg, &c->lay, c->offsets.data());
   c->stream = (hipStream_t)cfg->stream;
   c->d_state = nullptr;
-  c->parity = 0;
+  c->d_table = nullptr;
   c->steps_since_outer = 0;
+  c->ok_grads = nullptr;
+  c->ok_grads_bytes = 0;
   c->have_scale = false;
   c->inv_scale = 1.0f;
   c->checked_flags = nullptr;
@@ -236,13 +253,15 @@ int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco
   if (prop.maxSharedMemoryPerMultiProcessor >= 64 * 1024)
     c->tune.lds_per_cu = (uint32_t)prop.maxSharedMemoryPerMultiProcessor;
 
-  rc = check_device_range(c, cfg->arena, c->lay.arena_bytes, "arena");
+  rc = check_device_range(c, c->device, cfg->arena, c->lay.arena_bytes, "arena");
   if (rc != DILOCO_OK) return bail(rc);
 
   const uint32_t k = cfg->k_workers;
-  e = hipMalloc(reinterpret_cast<void**>(&c->d_state), 2 * k * sizeof(RepState));
+  // One allocation: the step state [k], then the per-step table [k].
+  e = hipMalloc(reinterpret_cast<void**>(&c->d_state), k * (sizeof(RepState) + sizeof(StepEntry)));
   if (e != hipSuccess) return bail(fail_hip(c, "hipMalloc(step state)", e));
-  std::vector<RepState> st(2 * k);
+  c->d_table = reinterpret_cast<StepEntry*>(c->d_state + k);
+  std::vector<RepState> st(k);
   for (auto& s : st) { s.p1 = 1.0; s.p2 = 1.0; s.step = 0; s.pad = 0; }
   e = hipMemcpyAsync(c->d_state, st.data(), st.size() * sizeof(RepState), hipMemcpyHostToDevice,
                      c->stream);
@@ -254,7 +273,7 @@ int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco
   if (init_params) {
     for (uint32_t t = 0; t < cfg->n_tensors; ++t) {
       if (!init_params[t]) return bail(fail(c, DILOCO_ERR_INVALID_ARG, "init_params[%u] is NULL", t));
-      rc = check_device_range(c, init_params[t], c->numel[t] * 4, "init_params[t]");
+      rc = check_device_range(c, c->device, init_params[t], c->numel[t] * 4, "init_params[t]");
       if (rc != DILOCO_OK) return bail(rc);
       e = hipMemcpyAsync(theta0 + c->offsets[t], init_params[t], c->numel[t] * 4,
                          hipMemcpyDeviceToDevice, c->stream);
@@ -286,7 +305,7 @@ int diloco_unscale_check(diloco_ctx* ctx, const void* grads, uint64_t grad_strid
   if (((uintptr_t)found_inf & 3u) != 0) return fail(ctx, DILOCO_ERR_ALIGN, "found_inf misaligned");
   if (!std::isfinite(inv_scale) || !(inv_scale > 0.0f))
     return fail(ctx, DILOCO_ERR_INVALID_ARG, "inv_scale must be finite and > 0");
-  rc = check_device_range(ctx, found_inf, ctx->cfg.k_workers * 4ull, "found_inf");
+  rc = check_device_range(ctx, ctx->device, found_inf, ctx->cfg.k_workers * 4ull, "found_inf");
   if (rc != DILOCO_OK) return rc;
   hipError_t e = launch_check(grads, grad_stride, ctx->lay.n_pad, (int)ctx->cfg.k_workers,
                               grad_dtype == DILOCO_F16, found_inf, ctx->tune, ctx->n_cu,
@@ -312,6 +331,11 @@ int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
       return fail(ctx, DILOCO_ERR_STATE,
                   "found_inf given without a preceding diloco_unscale_check of these gradients");
     inv_scale = ctx->inv_scale;
+  } else if (grad_dtype == DILOCO_F16) {
+    // binary16 gradients exist only under a loss scale: stepping them unchecked and unscaled
+    // would corrupt the weights silently
+    return fail(ctx, DILOCO_ERR_STATE,
+                "binary16 gradients need the found_inf flags of a preceding diloco_unscale_check");
   }
   const diloco_config& cf = ctx->cfg;
   const uint32_t k = cf.k_workers;
@@ -323,12 +347,8 @@ int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
   a.stride = ctx->lay.stride;
   a.g_stride = grad_stride;
   a.n_pad = ctx->lay.n_pad;
-  a.found_inf = found_inf;
-  a.st_cur = ctx->d_state + (size_t)ctx->parity * k;
-  a.st_nxt = ctx->d_state + (size_t)(ctx->parity ^ 1) * k;
+  a.table = ctx->d_table;
   // Each scalar is formed in double and rounded to float once.
-  a.beta1d = cf.beta1;
-  a.beta2d = cf.beta2;
   a.beta1 = (float)cf.beta1;
   a.beta2 = (float)cf.beta2;
   a.omb1 = (float)(1.0 - cf.beta1);
@@ -343,10 +363,12 @@ int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
     a.lr_g[q] = used ? (float)(lr * ctx->lr_scale[q]) : 0.0f;
     a.lr_wd_g[q] = used ? (float)(lr * ctx->lr_scale[q] * ctx->group_wd[q]) : 0.0f;
   }
-  hipError_t e = launch_inner(a, (int)k, grad_dtype == DILOCO_F16, ctx->n_groups != 0, ctx->tune,
-                              ctx->n_cu, ctx->stream);
+  hipError_t e = launch_prologue(ctx->d_state, ctx->d_table, found_inf, cf.beta1, cf.beta2, (int)k,
+                                 ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, "step prologue launch", e);
+  e = launch_inner(a, (int)k, grad_dtype == DILOCO_F16, ctx->n_groups != 0, ctx->tune,
+                   ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, "inner step launch", e);
-  ctx->parity ^= 1;
   ctx->have_scale = false;
   ctx->steps_since_outer += 1;
   if (cf.h_inner_steps != 0 && ctx->steps_since_outer % cf.h_inner_steps == 0)
@@ -377,7 +399,7 @@ int diloco_set_param_groups(diloco_ctx* ctx, const uint8_t* group_of_tensor, uin
   // One group id per 64-element chunk; a chunk never holds elements of two tensors because
   // every tensor starts on a 64-element boundary.  Chunks of pure padding take group 0.
   const uint64_t n_chunks = ctx->lay.n_pad / DILOCO_TENSOR_ALIGN;
-  std::vector<uint8_t> map(n_chunks, 0);
+  std::vector<uint8_t> map(n_chunks, 0);  // n_chunks is a multiple of 128: whole 32-bit words
   for (uint32_t t = 0; t < nt; ++t) {
     const uint64_t first = ctx->offsets[t] / DILOCO_TENSOR_ALIGN;
     const uint64_t last = (ctx->offsets[t] + ctx->numel[t] - 1) / DILOCO_TENSOR_ALIGN;
@@ -423,10 +445,11 @@ int diloco_outer_step(diloco_ctx* ctx) {
   a.lr = (float)ctx->cfg.outer_lr;
   a.mu = (float)ctx->cfg.outer_momentum;
   a.kf = (float)ctx->cfg.k_workers;
+  a.inv_kf = 1.0f / a.kf;  // exact when k is a power of two, the only case that uses it
   a.k = (int)ctx->cfg.k_workers;
   a.pg = ctx->cfg.pg_dtype;
   a.round_mean = ctx->cfg.pg_round_mean;
-  hipError_t e = launch_outer(a, ctx->tune, ctx->n_cu, ctx->stream);
+  hipError_t e = launch_outer(a, ctx->tune, ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, "outer step launch", e);
   ctx->steps_since_outer = 0;
   return DILOCO_OK;
@@ -461,8 +484,7 @@ int diloco_get_steps(diloco_ctx* ctx, uint32_t* steps) {
   std::vector<RepState> st(k);
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e == hipSuccess)
-    e = hipMemcpy(st.data(), ctx->d_state + (size_t)ctx->parity * k, k * sizeof(RepState),
-                  hipMemcpyDeviceToHost);
+    e = hipMemcpy(st.data(), ctx->d_state, k * sizeof(RepState), hipMemcpyDeviceToHost);
   if (e != hipSuccess) return fail_hip(ctx, "reading step counts", e);
   for (uint32_t r = 0; r < k; ++r) steps[r] = (uint32_t)st[r].step;
   return DILOCO_OK;
@@ -481,9 +503,9 @@ int diloco_cast_f32_to_bf16(const float* in, uint16_t* out, uint64_t n, void* st
 static int cast_common(const float* in, uint16_t* out, uint64_t n, int pg, void* stream) {
   if (n == 0) return DILOCO_OK;
   if (!in || !out) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "NULL argument");
-  int rc = check_device_range(nullptr, in, n * 4, "in");
+  int rc = check_device_range(nullptr, -1, in, n * 4, "in");
   if (rc != DILOCO_OK) return rc;
-  rc = check_device_range(nullptr, out, n * 2, "out");
+  rc = check_device_range(nullptr, -1, out, n * 2, "out");
   if (rc != DILOCO_OK) return rc;
   hipError_t e = launch_cast(in, out, n, pg, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(nullptr, "cast launch", e);
@@ -494,16 +516,16 @@ int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value) {
   if (!ctx || !name) return fail(ctx, DILOCO_ERR_INVALID_ARG, "NULL argument");
   Tuning& t = ctx->tune;
   const std::string n(name);
-  if (n == "inner_vec" && (value == 1 || value == 4)) t.inner_vec = value;
-  else if (n == "inner_block" && (value == 64 || value == 256)) t.inner_block = value;
+  const bool block_ok = value == 64 || value == 128 || value == 256;
+  if (n == "inner_block" && block_ok) t.inner_block = value;
+  else if (n == "outer_block" && block_ok) t.outer_block = value;
   else if (n == "inner_waves" && value >= -1 && value <= 32) t.inner_waves = value;
   else if (n == "outer_waves" && value >= -1 && value <= 32) t.outer_waves = value;
-  else if (n == "inner_nt" && (value == 0 || value == 1)) t.inner_nt = value;
+  else if (n == "outer_anyk" && (value == 0 || value == 1)) t.outer_anyk = value;
   else if (n == "check_block" && (value == 64 || value == 256)) t.check_block = value;
   else if (n == "check_vec" && (value == 1 || value == 2 || value == 4 || value == 8)) t.check_vec = value;
   else if (n == "check_waves" && value >= 0 && value <= 32) t.check_waves = value;
   else if (n == "check_persist" && value >= 0 && value <= 64) t.check_persist = value;
-  else if (n == "xcd_remap" && (value == 0 || value == 1)) t.xcd_remap = value;
   else return fail(ctx, DILOCO_ERR_INVALID_ARG, "unknown tuning knob or value: %s=%d", name, value);
   return DILOCO_OK;
 }

@@ -23,7 +23,6 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBlock = 256;         // 4 wavefronts of 64 lanes
 constexpr int kVecElems = 4;        // floats per 128-bit access
-constexpr int kXcds = 8;
 
 template <bool NT, class T>
 __device__ __forceinline__ T ld(const T* p) {
@@ -42,17 +41,6 @@ __device__ __forceinline__ void st(T* p, T x) {
 // shared memory that the kernel never touches.
 extern __shared__ float occupancy_pad[];
 
-// Tile handled by this workgroup (one tile per workgroup: many small workgroups in dispatch
-// order keep every stream's in-flight addresses in a tight window, which measured faster than
-// any grid-stride variant).  With xcd_remap the hardware's round-robin of consecutive
-// workgroups over the 8 XCDs is undone so that each XCD walks one contiguous range of tiles
-// (gridDim.x is then a multiple of 8 and may exceed the tile count).
-__device__ __forceinline__ uint32_t tile_of_block(bool xcd_remap) {
-  const uint32_t b = blockIdx.x;
-  if (!xcd_remap) return b;
-  return (b % kXcds) * (gridDim.x / kXcds) + b / kXcds;
-}
-
 // ------------------------------------------------------------------------------------------
 // Inner optimizer: AdamW over all k workers, grid = (tile blocks, k).
 // (Section "Implementation": the inner optimizer is AdamW, one step per training step.)
@@ -70,15 +58,54 @@ __device__ __forceinline__ void adamw_elem(float& th, float& m, float& v, float 
   v = vi;
 }
 
-template <int B, int V, bool G16, bool NT, bool GROUPS, bool REMAP>
-__global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32_t tiles) {
-  const uint32_t r = blockIdx.y;
-  // Without the XCD remap the grid holds exactly one workgroup per tile: no bounds check, so
-  // the first vector loads wait for a single batch of kernel-argument loads only.
-  const uint32_t tile = tile_of_block(REMAP);
-  if constexpr (REMAP) {
-    if (tile >= tiles) return;
+// Step prologue: one thread per worker.  A worker whose found_inf flag is set takes no step:
+// its step state stays as it is and its table entry says "inactive".  Otherwise the running
+// products beta^t (double) and the step count advance in place, and the table receives the
+// bias corrections 1 - beta^t rounded to float once.  Because the state lives on the device
+// and is advanced by this kernel, a captured launch sequence replays correctly any number of
+// times.
+__global__ __launch_bounds__(64) void step_prologue_kernel(RepState* __restrict__ state,
+                                                           StepEntry* __restrict__ table,
+                                                           const int32_t* __restrict__ found_inf,
+                                                           double beta1, double beta2, int k) {
+  const int r = (int)threadIdx.x;
+  if (r >= k) return;
+  const bool skip = found_inf != nullptr && found_inf[r] != 0;
+  RepState rs = state[r];
+  if (!skip) {
+    rs.p1 *= beta1;
+    rs.p2 *= beta2;
+    rs.step += 1;
+    state[r] = rs;
   }
+  StepEntry e;
+  e.bc1 = (float)(1.0 - rs.p1);  // 1 - beta1^t
+  e.bc2 = (float)(1.0 - rs.p2);  // 1 - beta2^t
+  e.active = skip ? 0 : 1;
+  e.pad = 0;
+  table[r] = e;
+}
+
+// The group's learning rate and lr*weight_decay (at most 8 groups; the 16 scalars sit in SGPRs).
+// With a wave-uniform q this is a chain of scalar selects; with a per-lane q, vector selects.
+__device__ __forceinline__ void select_group(const InnerArgs& a, uint32_t q, float& lr,
+                                             float& lr_wd) {
+  lr = a.lr_g[0];
+  lr_wd = a.lr_wd_g[0];
+#pragma unroll
+  for (uint32_t j = 1; j < 8; ++j) {
+    lr = q == j ? a.lr_g[j] : lr;
+    lr_wd = q == j ? a.lr_wd_g[j] : lr_wd;
+  }
+}
+
+// One 128-bit vector per lane per stream; a wave covers 256 consecutive elements, a workgroup
+// of B threads B*4.  The grid holds exactly one workgroup per tile: no bounds check.
+template <int B, bool G16, bool GROUPS>
+__global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32_t tiles) {
+  constexpr bool NT = true;
+  const uint32_t r = blockIdx.y;
+  const uint32_t tile = blockIdx.x;
 
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta + (size_t)r * a.stride);
   f32x4* __restrict__ m_p = reinterpret_cast<f32x4*>(a.m + (size_t)r * a.stride);
@@ -88,82 +115,55 @@ __global__ __launch_bounds__(B) void adamw_flat_kernel(const InnerArgs a, uint32
   const u32x2* __restrict__ g16_p =
       reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(a.g) + (size_t)r * a.g_stride);
 
-  // The tile's loads are issued before the worker's step state is read, so that the state's
-  // dependent scalar loads overlap the HBM latency instead of preceding it.
-  const size_t base = (size_t)tile * (B * V) + threadIdx.x;
-  f32x4 th[V], m[V], v[V], g[V];
-  u32x2 graw[V];
-  uint8_t grp[V];
-#pragma unroll
-  for (int j = 0; j < V; ++j) {
-    const size_t i = base + (size_t)j * B;
-    if constexpr (G16) graw[j] = ld<NT>(g16_p + i);
-    else g[j] = ld<NT>(g32_p + i);
-    th[j] = ld<NT>(th_p + i);
-    m[j] = ld<NT>(m_p + i);
-    v[j] = ld<NT>(v_p + i);
-    // A lane's four elements lie inside one 64-element chunk, and a chunk holds one tensor.
-    // With single-wave workgroups a row of the tile is 4 chunks = one 32-bit word of the chunk
-    // map at a wave-uniform address: a scalar load, no extra vector memory instruction.
-    if constexpr (GROUPS) {
-      if constexpr (B == 64) {
-        const uint32_t word =
-            reinterpret_cast<const uint32_t*>(a.chunk_group)[(size_t)tile * V + j];
-        grp[j] = (uint8_t)(word >> ((threadIdx.x >> 4) * 8));
-      } else {
-        grp[j] = a.chunk_group[i >> 4];
-      }
-    }
-  }
+  // The tile's loads go out first; the worker's table entry and the tile's group word are
+  // wave-uniform scalar loads that overlap the HBM latency.
+  const size_t i = (size_t)tile * B + threadIdx.x;
+  f32x4 th, m, v, g;
+  u32x2 graw;
+  if constexpr (G16) graw = ld<NT>(g16_p + i);
+  else g = ld<NT>(g32_p + i);
+  th = ld<NT>(th_p + i);
+  m = ld<NT>(m_p + i);
+  v = ld<NT>(v_p + i);
 
-  // Worker r's step state.  A worker whose found_inf flag is set takes no step at all: its
-  // weights, moments and step count stay as they are.
-  const bool skip = a.found_inf != nullptr && a.found_inf[r] != 0;
-  RepState rs = a.st_cur[r];
-  if (!skip) {
-    rs.p1 *= a.beta1d;
-    rs.p2 *= a.beta2d;
-    rs.step += 1;
+  const StepEntry e = a.table[r];
+  // A lane's four elements lie inside one 64-element chunk, and a chunk holds one tensor.  A
+  // wave's 256 elements are 4 chunks = one 32-bit word of the chunk map.
+  uint32_t word = 0;
+  if constexpr (GROUPS) {
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    word = a.chunk_group[(size_t)tile * (B / 64) + wave];
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0) a.st_nxt[r] = rs;
-  if (skip) return;
-  const float bc1 = (float)(1.0 - rs.p1);  // 1 - beta1^t
-  const float bc2 = (float)(1.0 - rs.p2);  // 1 - beta2^t
+  // A worker whose found_inf flag was set takes no step at all: weights and moments stay.
+  if (!e.active) return;
 
-#pragma unroll
-  for (int j = 0; j < V; ++j) {
-    if constexpr (G16) {
-      f16x4 h;
-      __builtin_memcpy(&h, &graw[j], 8);
-      g[j] = __builtin_convertvector(h, f32x4) * a.inv_scale;
-    }
-    float lr = a.lr, lr_wd = a.lr_wd;
-    if constexpr (GROUPS) {
-      // select the group's scalars (they sit in SGPRs; at most 8 groups)
-      lr = a.lr_g[0];
-      lr_wd = a.lr_wd_g[0];
-#pragma unroll
-      for (int q = 1; q < 8; ++q) {
-        lr = grp[j] == q ? a.lr_g[q] : lr;
-        lr_wd = grp[j] == q ? a.lr_wd_g[q] : lr_wd;
-      }
-    }
-#pragma unroll
-    for (int c = 0; c < kVecElems; ++c) {
-      float t = th[j][c], mm = m[j][c], vv = v[j][c];
-      adamw_elem(t, mm, vv, g[j][c], a, lr, lr_wd, bc1, bc2);
-      th[j][c] = t;
-      m[j][c] = mm;
-      v[j][c] = vv;
+  if constexpr (G16) {
+    f16x4 h;
+    __builtin_memcpy(&h, &graw, 8);
+    g = __builtin_convertvector(h, f32x4);
+  }
+  g = g * a.inv_scale;  // 1.0 unless a scaler check recorded a factor (exact then)
+
+  float lr = a.lr, lr_wd = a.lr_wd;
+  if constexpr (GROUPS) {
+    // Almost every wave lies inside one tensor: all four chunk ids equal, scalar selects.
+    if (word == (word & 0xffu) * 0x01010101u) {
+      select_group(a, word & 0xffu, lr, lr_wd);
+    } else {
+      select_group(a, (word >> (((threadIdx.x & 63u) >> 4) * 8)) & 0xffu, lr, lr_wd);
     }
   }
 #pragma unroll
-  for (int j = 0; j < V; ++j) {
-    const size_t i = base + (size_t)j * B;
-    st<NT>(th_p + i, th[j]);
-    st<NT>(m_p + i, m[j]);
-    st<NT>(v_p + i, v[j]);
+  for (int c = 0; c < kVecElems; ++c) {
+    float t = th[c], mm = m[c], vv = v[c];
+    adamw_elem(t, mm, vv, g[c], a, lr, lr_wd, e.bc1, e.bc2);
+    th[c] = t;
+    m[c] = mm;
+    v[c] = vv;
   }
+  st<NT>(th_p + i, th);
+  st<NT>(m_p + i, m);
+  st<NT>(v_p + i, v);
   if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
@@ -193,17 +193,28 @@ __device__ __forceinline__ void nesterov_elem(float& th0, float& b, float dbar, 
   b = bn;
 }
 
-// One single-wave workgroup per 256-element tile: all K+2 loads in flight, then the arithmetic,
-// then K+2 stores.  RM: the average is rounded through the pseudo-gradient type as well.
-template <int K, int PG, bool RM>
-__global__ __launch_bounds__(64) void outer_fused_kernel(const OuterArgs a, uint32_t tiles) {
+// sum / k.  For a power-of-two k the quotient and the product with the exactly representable
+// 1/k are the same real number, hence the same correctly rounded float (subnormal results
+// included); the product costs one instruction instead of an IEEE division sequence.
+template <bool POW2>
+__device__ __forceinline__ float mean_of_sum(float s, const OuterArgs& a) {
+  if constexpr (POW2) return s * a.inv_kf;
+  else return s / a.kf;
+}
+
+// B/64 waves per workgroup, each wave one 256-element tile: all K+2 loads in flight, then the
+// arithmetic, then K+2 stores.  Two waves per workgroup put 2 KiB of every stream in flight from
+// one CU at the same moment, which measured 1-2.5 points faster than single-wave workgroups.
+// RM: the average is rounded through the pseudo-gradient type as well.
+template <int K, int PG, bool RM, int B>
+__global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint32_t tiles) {
   constexpr bool NT = true;
-  const uint32_t tile = blockIdx.x;  // the grid holds exactly one workgroup per tile
+  constexpr bool POW2 = (K & (K - 1)) == 0;
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
   const size_t rstride = a.stride / kVecElems;  // replica stride in vectors
-  const size_t i = (size_t)tile * 64 + threadIdx.x;
+  const size_t i = (size_t)blockIdx.x * B + threadIdx.x;  // one workgroup per B*4 elements
   f32x4 t0 = ld<NT>(t0_p + i);
   f32x4 b = ld<NT>(b_p + i);
   f32x4 th[K];
@@ -214,7 +225,7 @@ __global__ __launch_bounds__(64) void outer_fused_kernel(const OuterArgs a, uint
     float s = pseudo_grad<PG>(t0[c], th[0][c]);
 #pragma unroll
     for (int r = 1; r < K; ++r) s = s + pseudo_grad<PG>(t0[c], th[r][c]);
-    float dbar = s / a.kf;
+    float dbar = mean_of_sum<POW2>(s, a);
     if constexpr (RM) dbar = round_through<PG>(dbar);
     float t = t0[c], bb = b[c];
     nesterov_elem(t, bb, dbar, a.lr, a.mu);
@@ -228,16 +239,15 @@ __global__ __launch_bounds__(64) void outer_fused_kernel(const OuterArgs a, uint
   if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
-// Any k (run-time loop over the workers): one single-wave workgroup per 256-element tile.
-template <int PG, bool RM>
-__global__ __launch_bounds__(64) void outer_fused_anyk_kernel(const OuterArgs a, uint32_t tiles) {
+// Any k (run-time loop over the workers).
+template <int PG, bool RM, int B>
+__global__ __launch_bounds__(B) void outer_fused_anyk_kernel(const OuterArgs a, uint32_t tiles) {
   constexpr bool NT = true;
-  const uint32_t tile = blockIdx.x;  // the grid holds exactly one workgroup per tile
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
   const size_t rstride = a.stride / kVecElems;
-  const size_t i = (size_t)tile * 64 + threadIdx.x;
+  const size_t i = (size_t)blockIdx.x * B + threadIdx.x;
   f32x4 t0 = ld<NT>(t0_p + i);
   f32x4 b = ld<NT>(b_p + i);
   f32x4 s;
@@ -252,9 +262,10 @@ __global__ __launch_bounds__(64) void outer_fused_anyk_kernel(const OuterArgs a,
 #pragma unroll
     for (int c = 0; c < kVecElems; ++c) s[c] = s[c] + pseudo_grad<PG>(t0[c], th[c]);
   }
+  const bool pow2 = (a.k & (a.k - 1)) == 0;
 #pragma unroll
   for (int c = 0; c < kVecElems; ++c) {
-    float dbar = s[c] / a.kf;
+    float dbar = pow2 ? mean_of_sum<true>(s[c], a) : mean_of_sum<false>(s[c], a);
     if constexpr (RM) dbar = round_through<PG>(dbar);
     float t = t0[c], bb = b[c];
     nesterov_elem(t, bb, dbar, a.lr, a.mu);
@@ -389,13 +400,12 @@ uint32_t pad_lds_bytes(int waves_per_cu, int block, uint32_t lds_per_cu) {
 }
 
 // Grid size in x for `tiles` tiles: one block per tile, or persist*n_cu grid-stride blocks.
-uint32_t grid_x(uint64_t tiles, int persist, int n_cu, bool xcd_remap) {
+uint32_t grid_x(uint64_t tiles, int persist, int n_cu) {
   uint64_t g = tiles;
   if (persist > 0) {
     const uint64_t cap = (uint64_t)persist * (uint64_t)n_cu;
     if (g > cap) g = cap;
   }
-  if (xcd_remap) g = (g + kXcds - 1) / kXcds * kXcds;
   if (g == 0) g = 1;
   return (uint32_t)g;
 }
@@ -405,98 +415,97 @@ uint32_t grid_x(uint64_t tiles, int persist, int n_cu, bool xcd_remap) {
 // ------------------------------------------------------------------------------------------
 // Launchers.  n_pad is a multiple of 8192 elements, so every tile size below divides it.
 // ------------------------------------------------------------------------------------------
-template <int B, int V, bool G16, bool NT, bool GROUPS>
-static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, int n_cu,
-                                 hipStream_t s) {
-  const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems * V);
-  const dim3 grid(grid_x(tiles, 0, n_cu, t.xcd_remap != 0), (uint32_t)k);
-  // The grouped variant's tile waits for one more dependent scalar load: 3 more waves.
-  const int waves = t.inner_waves < 0 ? auto_waves_inner((G16 ? 3584 : 4096) * V) + (GROUPS ? 3 : 0)
-                                      : t.inner_waves;
-  const uint32_t lds = pad_lds_bytes(waves, B, t.lds_per_cu);
-  if (t.xcd_remap)
-    hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT, GROUPS, true>), grid, dim3(B), lds, s, a,
-                       (uint32_t)tiles);
-  else
-    hipLaunchKernelGGL((adamw_flat_kernel<B, V, G16, NT, GROUPS, false>), grid, dim3(B), lds, s,
-                       a, (uint32_t)tiles);
+hipError_t launch_prologue(RepState* state, StepEntry* table, const int32_t* found_inf,
+                           double beta1, double beta2, int k, hipStream_t s) {
+  hipLaunchKernelGGL(step_prologue_kernel, dim3(1), dim3(64), 0, s, state, table, found_inf, beta1,
+                     beta2, k);
   return hipGetLastError();
 }
 
-template <int B, bool G16, bool NT, bool GROUPS>
-static hipError_t launch_inner_b(const InnerArgs& a, int k, const Tuning& t, int n_cu,
-                                 hipStream_t s) {
-  if (t.inner_vec == 4) return launch_inner_t<B, 4, G16, NT, GROUPS>(a, k, t, n_cu, s);
-  return launch_inner_t<B, 1, G16, NT, GROUPS>(a, k, t, n_cu, s);
-}
-
-template <bool G16, bool NT, bool GROUPS>
-static hipError_t launch_inner_v(const InnerArgs& a, int k, const Tuning& t, int n_cu,
-                                 hipStream_t s) {
-  if (t.inner_block == 256) return launch_inner_b<256, G16, NT, GROUPS>(a, k, t, n_cu, s);
-  return launch_inner_b<64, G16, NT, GROUPS>(a, k, t, n_cu, s);
-}
-
-template <bool G16, bool GROUPS>
-static hipError_t launch_inner_n(const InnerArgs& a, int k, const Tuning& t, int n_cu,
-                                 hipStream_t s) {
-  return t.inner_nt ? launch_inner_v<G16, true, GROUPS>(a, k, t, n_cu, s)
-                    : launch_inner_v<G16, false, GROUPS>(a, k, t, n_cu, s);
-}
-
-hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const Tuning& t,
-                        int n_cu, hipStream_t s) {
-  if (groups) return g16 ? launch_inner_n<true, true>(a, k, t, n_cu, s)
-                         : launch_inner_n<false, true>(a, k, t, n_cu, s);
-  return g16 ? launch_inner_n<true, false>(a, k, t, n_cu, s)
-             : launch_inner_n<false, false>(a, k, t, n_cu, s);
-}
-
-template <int K, int PG, bool RM>
-static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
-  const uint64_t tiles = a.n_pad / (uint64_t)(64 * kVecElems);
-  // With only ~4 waves resident (k >= 7) the conversions of the reduced-precision modes lengthen
-  // each wave's compute phase enough to under-fill the memory pipe: two more waves measured
-  // +0.5...0.9 % there (k = 8), and -2 % at smaller k, where more waves are resident anyway.
-  int waves = t.outer_waves;
-  if (waves < 0) {
-    waves = auto_waves_outer(K);
-    if (PG != 0 && waves <= 4) waves += 2;
-  }
-  const uint32_t lds = pad_lds_bytes(waves, 64, t.lds_per_cu);
-  hipLaunchKernelGGL((outer_fused_kernel<K, PG, RM>), dim3((uint32_t)tiles), dim3(64), lds, s, a,
+template <int B, bool G16, bool GROUPS>
+static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, hipStream_t s) {
+  const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
+  const dim3 grid((uint32_t)tiles, (uint32_t)k);
+  const int waves = t.inner_waves < 0 ? auto_waves_inner(G16 ? 3584 : 4096) : t.inner_waves;
+  const uint32_t lds = pad_lds_bytes(waves, B, t.lds_per_cu);
+  hipLaunchKernelGGL((adamw_flat_kernel<B, G16, GROUPS>), grid, dim3(B), lds, s, a,
                      (uint32_t)tiles);
   return hipGetLastError();
 }
 
-template <int PG, bool RM>
-static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, hipStream_t s) {
-  switch (a.k) {
-    case 1: return launch_outer_t<1, PG, RM>(a, t, s);
-    case 2: return launch_outer_t<2, PG, RM>(a, t, s);
-    case 3: return launch_outer_t<3, PG, RM>(a, t, s);
-    case 4: return launch_outer_t<4, PG, RM>(a, t, s);
-    case 5: return launch_outer_t<5, PG, RM>(a, t, s);
-    case 6: return launch_outer_t<6, PG, RM>(a, t, s);
-    case 7: return launch_outer_t<7, PG, RM>(a, t, s);
-    case 8: return launch_outer_t<8, PG, RM>(a, t, s);
-    default: {
-      const uint64_t tiles = a.n_pad / (uint64_t)(64 * kVecElems);
-      const int waves = t.outer_waves < 0 ? auto_waves_outer(a.k) : t.outer_waves;
-      hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM>), dim3((uint32_t)tiles), dim3(64),
-                         pad_lds_bytes(waves, 64, t.lds_per_cu), s, a, (uint32_t)tiles);
-      return hipGetLastError();
-    }
+template <bool G16, bool GROUPS>
+static hipError_t launch_inner_b(const InnerArgs& a, int k, const Tuning& t, hipStream_t s) {
+  switch (t.inner_block) {
+    case 256: return launch_inner_t<256, G16, GROUPS>(a, k, t, s);
+    case 128: return launch_inner_t<128, G16, GROUPS>(a, k, t, s);
+    default: return launch_inner_t<64, G16, GROUPS>(a, k, t, s);
   }
 }
 
-hipError_t launch_outer(const OuterArgs& a, const Tuning& t, int n_cu, hipStream_t s) {
-  (void)n_cu;
+hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const Tuning& t,
+                        hipStream_t s) {
+  if (groups) return g16 ? launch_inner_b<true, true>(a, k, t, s)
+                         : launch_inner_b<false, true>(a, k, t, s);
+  return g16 ? launch_inner_b<true, false>(a, k, t, s) : launch_inner_b<false, false>(a, k, t, s);
+}
+
+// Resident waves per CU of the outer step.  With only ~4 waves resident (k >= 7) the conversions
+// of the reduced-precision modes lengthen each wave's compute phase enough to under-fill the
+// memory pipe: two more waves measured +0.5...0.9 % there (k = 8), and -2 % at smaller k, where
+// more waves are resident anyway.
+static int outer_waves(const Tuning& t, int k, int pg) {
+  if (t.outer_waves >= 0) return t.outer_waves;
+  int waves = auto_waves_outer(k);
+  if (pg != 0 && waves <= 4) waves += 2;
+  return waves;
+}
+
+template <int K, int PG, bool RM, int B>
+static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
+  const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
+  const uint32_t lds = pad_lds_bytes(outer_waves(t, K, PG), B, t.lds_per_cu);
+  hipLaunchKernelGGL((outer_fused_kernel<K, PG, RM, B>), dim3((uint32_t)tiles), dim3(B), lds, s, a,
+                     (uint32_t)tiles);
+  return hipGetLastError();
+}
+
+template <int PG, bool RM, int B>
+static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, hipStream_t s) {
+  if (!t.outer_anyk) {
+    switch (a.k) {
+      case 1: return launch_outer_t<1, PG, RM, B>(a, t, s);
+      case 2: return launch_outer_t<2, PG, RM, B>(a, t, s);
+      case 3: return launch_outer_t<3, PG, RM, B>(a, t, s);
+      case 4: return launch_outer_t<4, PG, RM, B>(a, t, s);
+      case 5: return launch_outer_t<5, PG, RM, B>(a, t, s);
+      case 6: return launch_outer_t<6, PG, RM, B>(a, t, s);
+      case 7: return launch_outer_t<7, PG, RM, B>(a, t, s);
+      case 8: return launch_outer_t<8, PG, RM, B>(a, t, s);
+      default: break;
+    }
+  }
+  const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
+  const uint32_t lds = pad_lds_bytes(outer_waves(t, a.k, PG), B, t.lds_per_cu);
+  hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM, B>), dim3((uint32_t)tiles), dim3(B), lds, s,
+                     a, (uint32_t)tiles);
+  return hipGetLastError();
+}
+
+template <int PG, bool RM>
+static hipError_t launch_outer_b(const OuterArgs& a, const Tuning& t, hipStream_t s) {
+  switch (t.outer_block) {
+    case 64: return launch_outer_k<PG, RM, 64>(a, t, s);
+    case 256: return launch_outer_k<PG, RM, 256>(a, t, s);
+    default: return launch_outer_k<PG, RM, 128>(a, t, s);
+  }
+}
+
+hipError_t launch_outer(const OuterArgs& a, const Tuning& t, hipStream_t s) {
   const bool rm = a.round_mean != 0;
   switch (a.pg) {
-    case 1: return rm ? launch_outer_k<1, true>(a, t, s) : launch_outer_k<1, false>(a, t, s);
-    case 2: return rm ? launch_outer_k<2, true>(a, t, s) : launch_outer_k<2, false>(a, t, s);
-    default: return launch_outer_k<0, false>(a, t, s);  // FP32: rounding the mean is a no-op
+    case 1: return rm ? launch_outer_b<1, true>(a, t, s) : launch_outer_b<1, false>(a, t, s);
+    case 2: return rm ? launch_outer_b<2, true>(a, t, s) : launch_outer_b<2, false>(a, t, s);
+    default: return launch_outer_b<0, false>(a, t, s);  // FP32: rounding the mean is a no-op
   }
 }
 
@@ -505,7 +514,7 @@ static hipError_t launch_check_t(const void* g, uint64_t g_stride, uint64_t n_pa
                                  int32_t* found_inf, const Tuning& t, int n_cu, hipStream_t s) {
   const uint64_t vec_elems = g16 ? 8 : 4;
   const uint64_t tiles = n_pad / (vec_elems * B * V);
-  const dim3 grid(grid_x(tiles, t.check_persist, n_cu, false), (uint32_t)k);
+  const dim3 grid(grid_x(tiles, t.check_persist, n_cu), (uint32_t)k);
   const uint32_t lds = pad_lds_bytes(t.check_waves, B, t.lds_per_cu);
   if (g16)
     hipLaunchKernelGGL((unscale_check_kernel<B, V, true>), grid, dim3(B), lds, s, g, g_stride,

@@ -43,7 +43,7 @@ class GpuSide:
         self.n_pad = self.dl.layout.n_pad
         self.grads = None
 
-    def gen_grads(self, step, f16=False, inject_replica=None, inject_period=0):
+    def gen_grads(self, step, f16=False, inject_replica=None, inject_period=0, sigma=G_SIGMA):
         torch = self.torch
         dt = torch.float16 if f16 else torch.float32
         if self.grads is None or self.grads.dtype != dt:
@@ -58,7 +58,7 @@ class GpuSide:
                                       inject_key=synth.key(synth.STREAM_NONFINITE) if inj else 0,
                                       inject_period=inject_period if inj else 0, stream=s)
             else:
-                synth.device_fill_f32(self.grads[r].data_ptr(), self.n_pad, key, G_SIGMA,
+                synth.device_fill_f32(self.grads[r].data_ptr(), self.n_pad, key, sigma,
                                       self.kind.data_ptr(), stream=s)
         return self.grads
 
@@ -176,8 +176,8 @@ class SampledCpuSide:
         self.o.groups = oracle.ParamGroups(starts, lens, g[starts.astype(np.int64)], lr_scale,
                                            weight_decay)
 
-    def gen_grads(self, step):
-        return [synth.host_gather_f32(self.idx, synth.key(synth.STREAM_GRADS, r, step), G_SIGMA,
+    def gen_grads(self, step, sigma=G_SIGMA):
+        return [synth.host_gather_f32(self.idx, synth.key(synth.STREAM_GRADS, r, step), sigma,
                                       self.kind_at) for r in range(self.k)]
 
 

@@ -70,10 +70,9 @@ def test_reduced_precision_pseudo_gradient_modes(k, pg, round_mean):
     gpu.dl.close()
 
 
-@pytest.mark.parametrize("tune", [dict(inner_block=256, inner_vec=4),
-                                  dict(inner_block=256, inner_vec=1, xcd_remap=1),
-                                  dict(inner_block=64, inner_vec=4, xcd_remap=1),
-                                  dict(inner_nt=0),
+@pytest.mark.parametrize("tune", [dict(inner_block=256, outer_block=256),
+                                  dict(inner_block=128, outer_block=64),
+                                  dict(inner_block=64, outer_block=128, outer_anyk=1),
                                   dict(inner_waves=0, outer_waves=0, check_waves=0),
                                   dict(inner_waves=3, outer_waves=16, check_block=64, check_vec=8,
                                        check_persist=2)])
@@ -187,7 +186,11 @@ def test_error_paths():
     assert code(lambda: D.diloco_unscale_check(dl.ctx, g.data_ptr(), g.stride(0), D.F32, 0.0,
                                                flags.data_ptr())) == D.ERR_INVALID_ARG
     assert code(lambda: D.diloco_get_buffer(dl.ctx, D.BUF_THETA, 2)) == D.ERR_INVALID_ARG
-    assert code(lambda: D.diloco_set_tuning(dl.ctx, "inner_vec", 3)) == D.ERR_INVALID_ARG
+    # binary16 gradients without the flags of a preceding check: refused, not stepped unscaled
+    g16 = dl.new_grads(torch.float16)
+    assert code(lambda: D.diloco_inner_step(dl.ctx, g16.data_ptr(), g16.stride(0), D.F16)) == D.ERR_STATE
+    assert "unscale_check" in D.diloco_last_error(dl.ctx)
+    assert code(lambda: D.diloco_set_tuning(dl.ctx, "inner_block", 96)) == D.ERR_INVALID_ARG
     assert code(lambda: D.diloco_set_tuning(dl.ctx, "no_such_knob", 1)) == D.ERR_INVALID_ARG
     assert "no_such_knob" in D.diloco_last_error(dl.ctx)
     # nothing was launched by any failed call

@@ -1,6 +1,8 @@
-"""The inner step enqueues one kernel and no memset, so an even number of inner steps can be
-captured into a HIP graph and replayed; every replay is checked against the oracle, with eager
-work and synchronisations between the replays."""
+"""Every entry point enqueues kernels only (no memset), and the per-worker step state is advanced
+on the device by the step's own prologue kernel, so any number of inner steps -- odd counts
+included -- can be captured into a HIP graph and replayed; every replay is checked against the
+oracle, with eager work (outer steps and single inner steps) and synchronisations between the
+replays."""
 import numpy as np
 import pytest
 
@@ -10,7 +12,8 @@ from harness import CpuSide, GpuSide, compare, compare_state
 pytestmark = pytest.mark.gpu
 
 
-def test_captured_pair_of_inner_steps_replays_correctly():
+@pytest.mark.parametrize("n_inner", [2, 3])
+def test_captured_inner_steps_replay_correctly(n_inner):
     import torch
     wl = synth.tiny()
     k = 2
@@ -27,23 +30,34 @@ def test_captured_pair_of_inner_steps_replays_correctly():
     with torch.cuda.graph(graph, stream=side):
         gpu.dl.unscale_check(g, 1.0, flags)
         gpu.dl.inner_step(g, flags=flags)
-        gpu.dl.inner_step(g)
+        for _ in range(n_inner - 1):
+            gpu.dl.inner_step(g)
     torch.cuda.synchronize()
     # capture itself executes nothing
     assert gpu.dl.steps() == [0, 0]
 
+    total = 0
     for replay in range(4):
         graph.replay()
         torch.cuda.synchronize()
-        cpu.o.inner_step(gc, found_inf_flags=[0, 0])
-        cpu.o.inner_step(gc)
+        cpu.o.inner_step(gc, found_inf_flags=[0, 0], inv_scale=1.0)
+        for _ in range(n_inner - 1):
+            cpu.o.inner_step(gc)
+        total += n_inner
         assert compare_state(gpu, cpu, 0, 0) == 0, "replay %d" % replay
         assert flags.cpu().tolist() == [0, 0]
-        # eager work of the same context between replays
+        # eager work of the same context between replays: an outer step, and on odd replays a
+        # single eager inner step (an odd number of eager steps between two replays)
         with torch.cuda.stream(side):
             gpu.dl.outer_step()
+            if replay % 2:
+                gpu.dl.inner_step(g)
         side.synchronize()
         cpu.o.outer_step()
+        if replay % 2:
+            cpu.o.inner_step(gc)
+            total += 1
         assert compare("theta0", gpu.host(gpu.dl.theta0), cpu.o.theta0, 0, 0) == 0
-    assert gpu.dl.steps() == [8, 8]
+        assert compare_state(gpu, cpu, 0, 0) == 0, "after eager work %d" % replay
+    assert gpu.dl.steps() == [total, total]
     gpu.dl.close()
