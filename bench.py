@@ -4,17 +4,19 @@
 One "step" is one DiLoCo round over synthetic inputs already resident in HBM: H fused AdamW
 inner steps of all k workers, then one fused outer step (pseudo-gradient, optional FP16
 rounding, mean over k, Nesterov SGD, broadcast).  The headline value is the algorithmic HBM
-traffic of the round divided by its wall time.  Per-kernel durations come from HIP events on
-the stream the kernels are launched on.
+traffic of the round divided by its wall time.  Every kernel launch of a timed region is
+bracketed by HIP events on the stream it is launched on, so each kernel is reported with the
+mean, median, minimum and maximum of its launch durations.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama150m|llama1.1b]
-                    [--h H] [--k K] [--pg f32|f16] [--no-also] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload tiny|llama150m|llama1.1b]
+                    [--h H] [--k K] [--pg f32|f16] [--no-also] [--no-cpu] [--tune name=value ...]
 
 Prints ONE JSON line.  Everything on this path is single-GPU: --gpus above 1 is refused.
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -33,168 +35,209 @@ def outer_bytes(n, k):
     return (16 + 8 * k) * n
 
 
-def median(xs):
-    xs = sorted(xs)
-    return xs[len(xs) // 2]
+def stats(ms, nbytes):
+    """Launch-duration statistics and the bandwidth figures that follow from them."""
+    s = sorted(ms)
+    mean, med = sum(s) / len(s), s[len(s) // 2]
+    return {"ms": mean, "ms_median": med, "ms_min": s[0], "ms_max": s[-1], "launches_timed": len(s),
+            "bytes": nbytes, "GBps": nbytes / mean / 1e6, "frac_of_peak": nbytes / mean / 1e6 / HBM_PEAK_GBS,
+            "frac_of_peak_median": nbytes / med / 1e6 / HBM_PEAK_GBS}
 
 
-def run_workload(name, k, H, pg_f16, rounds, warmup, torch, D, synth, groups=False):
-    wl = synth.WORKLOADS[name]()
-    n = wl.n_params
-    stream = torch.cuda.current_stream()
+class Bench:
+    """All device memory of the run comes out of ONE allocation made at start-up and is handed
+    out again leg after leg.  The driver clears freed device memory in the background (measured
+    here: about 34 GB/s, for as long as it takes), and while it does, every kernel loses 1-4 % of
+    its bandwidth; a benchmark that frees and re-allocates its buffers between legs measures
+    that, not the kernels."""
 
-    def fill(theta0, layout, offsets):
-        kind = torch.from_numpy(wl.kind_map(offsets, layout.n_pad)).to(theta0.device)
-        synth.device_fill_f32(theta0.data_ptr(), layout.n_pad, synth.key(synth.STREAM_WEIGHTS),
-                              0.02, kind.data_ptr(), ones_as_one=True, stream=stream.cuda_stream)
-        fill.kind = kind
+    def __init__(self, torch, D, synth, tune, pool_bytes):
+        self.torch, self.D, self.synth, self.tune = torch, D, synth, tune
+        self.stream = torch.cuda.current_stream()
+        self.pool = torch.empty(pool_bytes, dtype=torch.uint8, device="cuda")
+        self.base = 0       # offset of the current leg's first buffer (placement_spread moves it)
+        self.cursor = 0
 
-    dl = D.DiLoCo(wl.numel, k, fill_theta0=fill, h_inner_steps=H,
-                  pg_dtype=D.F16 if pg_f16 else D.F32)
-    if groups:
-        # matrices decay 0.1; norm vectors and the embedding / LM head: no decay, and the
-        # embeddings at half the learning rate
-        grp = [1 if v else 0 for v in wl.is_vector]
-        grp[-1] = 2
-        if name == "llama1.1b":
-            grp[-2] = 2
-        dl.set_param_groups(grp, [1.0, 1.0, 0.5], [0.1, 0.0, 0.0])
-    grads = dl.new_grads()
-    for r in range(k):  # one seeded gradient set ~N(0, 1e-3), resident for the whole run
-        synth.device_fill_f32(grads[r].data_ptr(), dl.layout.n_pad,
-                              synth.key(synth.STREAM_GRADS, r, 0), 1e-3, fill.kind.data_ptr(),
-                              stream=stream.cuda_stream)
-    del fill.kind
-    torch.cuda.synchronize()
+    def take(self, nbytes, dtype):
+        """The next nbytes of the pool (2 MiB-aligned, as large allocations are) as a tensor."""
+        start = (self.cursor + (1 << 21) - 1) >> 21 << 21
+        assert start + nbytes <= self.pool.numel(), "benchmark pool too small"
+        self.cursor = start + nbytes
+        return self.pool[start:start + nbytes].view(dtype)
 
-    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    def reset(self):
+        self.cursor = self.base
 
-    def one_round(timed):
-        marks = (ev(), ev(), ev()) if timed else None
-        if timed:
-            marks[0].record(stream)
-        rc = 0
-        for _ in range(H):
-            rc = dl.inner_step(grads)
-        assert rc == D.ROUND_COMPLETE
-        if timed:
-            marks[1].record(stream)
-        dl.outer_step()
-        if timed:
-            marks[2].record(stream)
-        return marks
+    # ------------------------------------------------------------------ set-up
+    def make(self, name, k, H=0, pg=0, round_mean=0, groups=False, g16=False):
+        """A context on the named workload with seeded synthetic weights (matrices ~N(0, 0.02),
+        norm vectors 1.0) and one resident seeded gradient set ~N(0, 1e-3) per worker."""
+        torch, D, synth = self.torch, self.D, self.synth
+        wl = synth.WORKLOADS[name]()
+        holder = {}
+        self.reset()
+        lay, _ = D.diloco_query_layout(D.make_config(wl.numel, k))
 
-    for _ in range(warmup):
-        one_round(False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    marks = [one_round(True) for _ in range(rounds)]
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    inner_ms = [m[0].elapsed_time(m[1]) / H for m in marks]
-    outer_ms = [m[1].elapsed_time(m[2]) for m in marks]
-    assert dl.steps() == [H * (rounds + warmup)] * k
-    finite = bool(torch.isfinite(dl.theta0).all())
-    dl.close()
-    del dl, grads
-    torch.cuda.empty_cache()
+        def fill(theta0, layout, offsets):
+            holder["kind"] = self.take(layout.n_pad, torch.uint8)
+            holder["kind"].copy_(torch.from_numpy(wl.kind_map(offsets, layout.n_pad)))
+            synth.device_fill_f32(theta0.data_ptr(), layout.n_pad, synth.key(synth.STREAM_WEIGHTS),
+                                  0.02, holder["kind"].data_ptr(), ones_as_one=True,
+                                  stream=self.stream.cuda_stream)
 
-    ib, ob = inner_bytes(n, k), outer_bytes(n, k)
-    im, om = sum(inner_ms) / len(inner_ms), sum(outer_ms) / len(outer_ms)
-    round_ms = wall_ms / rounds
-    return {
-        "workload": name, "n_params": n, "k": k, "H": H, "pg_dtype": "f16" if pg_f16 else "f32",
-        "finite": finite,
-        "round_ms": round_ms,
-        "round_GBps": (H * ib + ob) / round_ms / 1e6,
-        "inner": {"ms": im, "ms_median_round": median(inner_ms), "bytes": ib,
-                  "GBps": ib / im / 1e6, "frac_of_peak": ib / im / 1e6 / HBM_PEAK_GBS,
-                  "launches_timed": H * rounds},
-        "outer": {"ms": om, "ms_median": median(outer_ms), "bytes": ob,
-                  "GBps": ob / om / 1e6, "frac_of_peak": ob / om / 1e6 / HBM_PEAK_GBS,
-                  "launches_timed": rounds},
-    }
+        dl = D.DiLoCo(wl.numel, k, fill_theta0=fill, h_inner_steps=H, pg_dtype=pg,
+                      pg_round_mean=round_mean, arena=self.take(lay.arena_bytes, torch.float32))
+        if self.tune:
+            dl.set_tuning(**self.tune)
+        if groups:
+            # matrices decay 0.1; norm vectors and the embedding / LM head: no decay, and the
+            # embeddings at half the learning rate
+            grp = [1 if v else 0 for v in wl.is_vector]
+            grp[-1] = 2
+            if name == "llama1.1b":
+                grp[-2] = 2
+            dl.set_param_groups(grp, [1.0, 1.0, 0.5], [0.1, 0.0, 0.0])
+        gdt = torch.float16 if g16 else torch.float32
+        grads = dl.new_grads(gdt, out=self.take(dl.grads_numel() * (2 if g16 else 4), gdt))
+        for r in range(k):
+            if g16:
+                synth.device_fill_f16(grads[r].data_ptr(), dl.layout.n_pad,
+                                      synth.key(synth.STREAM_GRADS, r, 0), holder["kind"].data_ptr(),
+                                      stream=self.stream.cuda_stream)
+            else:
+                synth.device_fill_f32(grads[r].data_ptr(), dl.layout.n_pad,
+                                      synth.key(synth.STREAM_GRADS, r, 0), 1e-3,
+                                      holder["kind"].data_ptr(), stream=self.stream.cuda_stream)
+        torch.cuda.synchronize()
+        return wl, dl, grads
 
+    def flush(self):
+        pass  # nothing is freed between legs: see the class comment
 
-def quick_measure(name, k, pg_dtype, round_mean, n_inner, n_outer, torch, D, synth):
-    """Short timing of both kernels for one (workload, k, pseudo-gradient mode): n_inner inner
-    launches and n_outer outer launches after two warm-up launches of each."""
-    wl = synth.WORKLOADS[name]()
-    n = wl.n_params
-    stream = torch.cuda.current_stream()
-    dl = D.DiLoCo(wl.numel, k, fill_theta0=lambda t, lay, off: t.normal_(0, 0.02),
-                  pg_dtype=pg_dtype, pg_round_mean=round_mean)
-    g = dl.new_grads()
-    g.normal_(0, 1e-3)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    for _ in range(2):
-        dl.inner_step(g)
-        dl.outer_step()
-    torch.cuda.synchronize()
-    ev[0].record(stream)
-    for _ in range(n_inner):
-        dl.inner_step(g)
-    ev[1].record(stream)
-    for _ in range(n_outer):
-        dl.outer_step()
-    ev[2].record(stream)
-    torch.cuda.synchronize()
-    im, om = ev[0].elapsed_time(ev[1]) / n_inner, ev[1].elapsed_time(ev[2]) / n_outer
-    dl.close()
-    del dl, g
-    torch.cuda.empty_cache()
-    ib, ob = inner_bytes(n, k), outer_bytes(n, k)
-    return {"inner_ms": im, "inner_GBps": ib / im / 1e6, "inner_frac": ib / im / 1e6 / HBM_PEAK_GBS,
-            "outer_ms": om, "outer_GBps": ob / om / 1e6, "outer_frac": ob / om / 1e6 / HBM_PEAK_GBS}
+    # ------------------------------------------------------------------ timing
+    def time_launches(self, fn, n):
+        """n calls of fn, each bracketed by events on the launch stream; -> list of ms."""
+        torch = self.torch
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        ev[0].record(self.stream)
+        for i in range(n):
+            fn()
+            ev[i + 1].record(self.stream)
+        ev[n].synchronize()
+        return [ev[i].elapsed_time(ev[i + 1]) for i in range(n)]
 
+    def rounds(self, name, k, H, pg, rounds, warmup_rounds, warmup_inner=None, extra_outer=0,
+               groups=False):
+        """`warmup_rounds` untimed rounds (of warmup_inner inner steps each, default H), then
+        `rounds` timed rounds of H inner steps + 1 outer step with every launch timed, then
+        `extra_outer` more timed outer steps (rounds with no inner steps, which the method
+        allows)."""
+        torch, D = self.torch, self.D
+        wl, dl, grads = self.make(name, k, H=H, pg=pg, groups=groups)
+        n = wl.n_params
+        for _ in range(warmup_rounds):
+            for _ in range(H if warmup_inner is None else warmup_inner):
+                dl.inner_step(grads)
+            dl.outer_step()
+        torch.cuda.synchronize()
+        inner_ms, outer_ms = [], []
+        t0 = time.perf_counter()
+        for _ in range(rounds):
+            inner_ms += self.time_launches(lambda: dl.inner_step(grads), H)
+            outer_ms += self.time_launches(dl.outer_step, 1)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        if extra_outer:
+            outer_ms += self.time_launches(dl.outer_step, extra_outer)
+        done = (H if warmup_inner is None else warmup_inner) * warmup_rounds + H * rounds
+        assert dl.steps() == [done] * k
+        finite = bool(torch.isfinite(dl.theta0).all())
+        dl.close()
+        del dl, grads
+        self.flush()
+        ib, ob = inner_bytes(n, k), outer_bytes(n, k)
+        round_ms = wall_ms / rounds
+        res = {"workload": name, "n_params": n, "k": k, "H": H,
+               "pg_dtype": {0: "f32", 1: "f16", 2: "bf16"}[pg], "finite": finite,
+               "round_ms": round_ms, "round_GBps": (H * ib + ob) / round_ms / 1e6,
+               "outer": stats(outer_ms, ob)}
+        if H:
+            res["inner"] = stats(inner_ms, ib)
+        return res
 
-def run_mixed_precision(k, reps, torch, D, synth):
-    """Rows a1 + a2 in mixed precision: binary16 gradients scaled by 65536 on the 150M set plus
-    2000 ragged tensors; the inf/NaN check, then the inner step with the unscale fused in."""
-    wl = synth.WORKLOADS["stress"]()
-    n = wl.n_params
-    stream = torch.cuda.current_stream()
-    holder = {}
+    def quick(self, name, k, pg=0, round_mean=0, n_inner=20, n_outer=20, groups=False, tune=None):
+        """Short timing of both kernels: n_inner inner and n_outer outer launches after two
+        warm-up launches of each."""
+        wl, dl, grads = self.make(name, k, pg=pg, round_mean=round_mean, groups=groups)
+        if tune:
+            dl.set_tuning(**tune)
+        n = wl.n_params
+        for _ in range(2):
+            dl.inner_step(grads)
+            dl.outer_step()
+        self.torch.cuda.synchronize()
+        out = {}
+        if n_inner:
+            out["inner"] = stats(self.time_launches(lambda: dl.inner_step(grads), n_inner),
+                                 inner_bytes(n, k))
+        if n_outer:
+            out["outer"] = stats(self.time_launches(dl.outer_step, n_outer), outer_bytes(n, k))
+        dl.close()
+        del dl, grads
+        self.flush()
+        return out
 
-    def fill(theta0, layout, offsets):
-        holder["kind"] = torch.from_numpy(wl.kind_map(offsets, layout.n_pad)).to(theta0.device)
-        synth.device_fill_f32(theta0.data_ptr(), layout.n_pad, synth.key(synth.STREAM_WEIGHTS),
-                              0.02, holder["kind"].data_ptr(), ones_as_one=True,
-                              stream=stream.cuda_stream)
+    def placement_spread(self, name, k, pg, n_inner, n_outer):
+        """The same measurement with the arena and the gradients placed at three different
+        offsets inside the pool (three different sets of physical pages)."""
+        runs = []
+        for spacer_mib in (0, 130, 1026):
+            self.base = spacer_mib << 20
+            q = self.quick(name, k, pg=pg, n_inner=n_inner, n_outer=n_outer)
+            self.base = 0
+            runs.append({"spacer_MiB": spacer_mib,
+                         "inner_frac_median": q["inner"]["frac_of_peak_median"],
+                         "outer_frac_median": q["outer"]["frac_of_peak_median"],
+                         "inner_ms_median": q["inner"]["ms_median"],
+                         "outer_ms_median": q["outer"]["ms_median"]})
+        return {"workload": "%s x %d workers, %s pseudo-gradient; %d inner + %d outer launches per "
+                            "placement (offsets 0, 130 and 1026 MiB inside the run's one device "
+                            "allocation)" % (name, k, {0: "f32", 1: "f16"}[pg], n_inner, n_outer),
+                "runs": runs,
+                "inner_frac_min": min(r["inner_frac_median"] for r in runs),
+                "inner_frac_max": max(r["inner_frac_median"] for r in runs),
+                "outer_frac_min": min(r["outer_frac_median"] for r in runs),
+                "outer_frac_max": max(r["outer_frac_median"] for r in runs)}
 
-    dl = D.DiLoCo(wl.numel, k, fill_theta0=fill)
-    kind = holder["kind"]
-    g = dl.new_grads(torch.float16)
-    for r in range(k):
-        synth.device_fill_f16(g[r].data_ptr(), dl.layout.n_pad, synth.key(synth.STREAM_GRADS, r, 0),
-                              kind.data_ptr(), stream=stream.cuda_stream)
-    flags = dl.new_flags()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps + 1)]
-    dl.unscale_check(g, 1.0 / 65536, flags)
-    dl.inner_step(g, flags=flags)
-    torch.cuda.synchronize()
-    ev[0].record(stream)
-    for i in range(reps):
+    def mixed_precision(self, k, reps):
+        """Rows a1 + a2 in mixed precision: binary16 gradients scaled by 65536 on the 150M set
+        plus 2000 ragged tensors; the inf/NaN check, then the inner step with the unscale fused."""
+        torch = self.torch
+        wl, dl, g = self.make("stress", k, g16=True)
+        n = wl.n_params
+        flags = dl.new_flags()
         dl.unscale_check(g, 1.0 / 65536, flags)
-        ev[2 * i + 1].record(stream)
         dl.inner_step(g, flags=flags)
-        ev[2 * i + 2].record(stream)
-    torch.cuda.synchronize()
-    chk = sum(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(reps)) / reps
-    inn = sum(ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(reps)) / reps
-    assert flags.cpu().tolist() == [0] * k and dl.steps() == [reps + 1] * k
-    dl.close()
-    del dl, g, kind
-    torch.cuda.empty_cache()
-    cb, ib = 2 * n * k, inner_bytes(n, k, g16=True)
-    return {"config": {"workload": "llama150m + 2000 ragged tensors x %d workers, FP16 gradients "
-                                   "scaled by 65536" % k, "n_params": n, "n_tensors": len(wl.shapes)},
-            "unscale_check": {"ms": chk, "bytes": cb, "GBps": cb / chk / 1e6,
-                              "frac_of_peak": cb / chk / 1e6 / HBM_PEAK_GBS,
-                              "note": "includes the flag-clearing launch"},
-            "inner_step_fp16_grads": {"ms": inn, "bytes": ib, "GBps": ib / inn / 1e6,
-                                      "frac_of_peak": ib / inn / 1e6 / HBM_PEAK_GBS},
-            "launches_timed": reps}
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps + 1)]
+        ev[0].record(self.stream)
+        for i in range(reps):
+            dl.unscale_check(g, 1.0 / 65536, flags)
+            ev[2 * i + 1].record(self.stream)
+            dl.inner_step(g, flags=flags)
+            ev[2 * i + 2].record(self.stream)
+        torch.cuda.synchronize()
+        chk = [ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(reps)]
+        inn = [ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(reps)]
+        assert flags.cpu().tolist() == [0] * k and dl.steps() == [reps + 1] * k
+        dl.close()
+        del dl, g
+        self.flush()
+        return {"config": {"workload": "llama150m + 2000 ragged tensors x %d workers, FP16 gradients "
+                                       "scaled by 65536" % k, "n_params": n, "n_tensors": len(wl.shapes)},
+                "unscale_check": dict(stats(chk, 2 * n * k), note="includes the flag-clearing launch"),
+                "inner_step_fp16_grads": dict(stats(inn, inner_bytes(n, k, g16=True)),
+                                              note="includes the step-prologue launch")}
 
 
 def cpu_baseline(k, log2_slice=25, inner_reps=100, outer_reps=100):
@@ -242,7 +285,6 @@ def cpu_baseline(k, log2_slice=25, inner_reps=100, outer_reps=100):
                   % (log2_slice, k, inner_reps, outer_reps),
         "inner_step_GBps": inner_bytes(n, k) / inner_s / 1e9,
         "outer_step_GBps": outer_bytes(n, k) / outer_s / 1e9,
-        "inner_step_ms_extrapolated_to_workload": None,
         "inner_ns_per_element_worker": inner_s / (n * k) * 1e9,
         "outer_ns_per_element": outer_s / n * 1e9,
         "seconds": t2 - t0,
@@ -251,13 +293,24 @@ def cpu_baseline(k, log2_slice=25, inner_reps=100, outer_reps=100):
 
 
 def load_traffic(root, kernel, workload):
-    """Measured HBM bytes per launch from the committed rocprofv3 --pmc summary, if present."""
+    """Measured HBM bytes per launch of `kernel` on `workload` from the committed rocprofv3 --pmc
+    summary, with where it comes from; (None, reason) when the file does not cover the case."""
     path = os.path.join(root, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
             t = json.load(f)
-        return t[workload][kernel]["bytes_per_launch"]
+        src = "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, measured at commit %s)" \
+            % t.get("measured_at_commit", "unknown")
+        return t[workload][kernel]["bytes_per_launch"], src
     except (OSError, KeyError, ValueError):
+        return None, "no committed counter summary covers this kernel and workload"
+
+
+def git_head(root):
+    try:
+        return subprocess.run(["git", "-C", root, "rev-parse", "--short", "HEAD"], capture_output=True,
+                              text=True, timeout=10).stdout.strip() or None
+    except Exception:
         return None
 
 
@@ -270,8 +323,10 @@ def main():
     ap.add_argument("--k", type=int, default=8)
     ap.add_argument("--h", type=int, default=500)
     ap.add_argument("--pg", default=None, choices=["f32", "f16"])
-    ap.add_argument("--no-also", action="store_true", help="skip the second headline workload")
+    ap.add_argument("--no-also", action="store_true", help="only the main workload's rounds")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--tune", nargs="*", default=[], metavar="NAME=VALUE",
+                    help="launch-shape knobs applied to every context (diloco_set_tuning)")
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MIB",
                     help="first run a plain copy kernel of this many MiB three times (reference "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -288,34 +343,46 @@ def main():
     import paper_2407_07852_amd as D
     import synth
     torch.cuda.set_device(0)
+    tune = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.tune}
+    # one device allocation for the whole run, sized for the largest leg (arena + FP32 gradients
+    # + the generator's kind map), the placement legs' largest offset and alignment slack
+    full = not args.no_also and args.workload == "llama150m"
+    big = synth.WORKLOADS["llama1.1b" if full else args.workload]()
+    kk = max(args.k, 8) if full else args.k
+    big_lay, _ = D.diloco_query_layout(D.make_config(big.numel, kk))
+    pool_bytes = (big_lay.arena_bytes + ((kk - 1) * big_lay.stride + big_lay.n_pad) * 4
+                  + big_lay.n_pad + (1100 << 20))
+    B = Bench(torch, D, synth, tune, pool_bytes)
 
     if args.calibration_copy:
         nb = args.calibration_copy << 20
         a = torch.zeros(nb // 4, device="cuda")
         b = torch.empty_like(a)
         for _ in range(3):
-            synth.device_copy(b.data_ptr(), a.data_ptr(), nb,
-                              torch.cuda.current_stream().cuda_stream)
+            synth.device_copy(b.data_ptr(), a.data_ptr(), nb, B.stream.cuda_stream)
         torch.cuda.synchronize()
         del a, b
         torch.cuda.empty_cache()
 
-    pg = args.pg or ("f16" if args.workload == "llama1.1b" else "f32")
-    main_res = run_workload(args.workload, args.k, args.h, pg == "f16", args.steps, args.warmup,
-                            torch, D, synth)
+    pgn = args.pg or ("f16" if args.workload == "llama1.1b" else "f32")
+    pg = D.F16 if pgn == "f16" else D.F32
+    main_res = B.rounds(args.workload, args.k, args.h, pg, args.steps, args.warmup)
     also = None
-    if not args.no_also and args.workload == "llama150m":
-        # the other configuration the metric is quoted on: 1.1B x 8, FP16 pseudo-gradient
-        also = run_workload("llama1.1b", args.k, args.h, True, 1, 0, torch, D, synth)
-        also["warmup_note"] = "no warm-up round; the first launches of 500 absorb it"
+    if full:
+        # the other configuration the metric is quoted on: 1.1B x 8, FP16 pseudo-gradient.  One
+        # short warm-up round (10 inner steps + 1 outer step), one timed round of H inner steps,
+        # then 20 more timed outer steps.
+        also = B.rounds("llama1.1b", args.k, args.h, D.F16, 1, 1, warmup_inner=10, extra_outer=20)
 
     def roof(res, which):
         r = res[which]
         kernel = "adamw_flat_kernel" if which == "inner" else "outer_fused_kernel"
+        traffic, src = load_traffic(root, kernel, res["workload"])
         return {"bound": "hbm", "kernel": kernel, "achieved": r["GBps"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": r["frac_of_peak"], "ms_per_launch": r["ms"],
-                "algorithmic_bytes_per_launch": r["bytes"],
-                "traffic": load_traffic(root, kernel, res["workload"])}
+                "ms_per_launch_median": r["ms_median"], "launches_timed": r["launches_timed"],
+                "algorithmic_bytes_per_launch": r["bytes"], "traffic": traffic,
+                "traffic_source": src}
 
     out = {
         "metric": "inner/outer step HBM GB/s (% of peak) + outer-step ms",
@@ -326,40 +393,66 @@ def main():
         "data": "synthetic (seeded bell-shaped weights ~N(0,0.02), norm vectors 1.0, one resident "
                 "gradient set ~N(0,1e-3) per worker)",
         "config": {"workload": "%s x %d workers, H=%d AdamW inner steps + 1 outer step, %s "
-                               "pseudo-gradient" % (main_res["workload"], args.k, args.h, pg),
+                               "pseudo-gradient" % (main_res["workload"], args.k, args.h, pgn),
                    "n_params": main_res["n_params"], "k_workers": args.k, "H": args.h,
-                   "pg_dtype": pg, "step": "one round = H inner launches + 1 outer launch"},
-        "inner_step": main_res["inner"], "outer_step": main_res["outer"],
-        "outer_step_ms": main_res["outer"]["ms"],
-        "roofline": roof(main_res, "inner"),
-        "roofline_outer": roof(main_res, "outer"),
+                   "pg_dtype": pgn, "step": "one round = H inner launches + 1 outer launch",
+                   "tuning_overrides": tune, "commit": git_head(root)},
+        "outer_step": main_res["outer"], "outer_step_ms": main_res["outer"]["ms"],
         "finite": main_res["finite"],
     }
-    if also is not None:
+    if "inner" in main_res:
+        out["inner_step"] = main_res["inner"]
+        out["roofline"] = roof(main_res, "inner")
+    out["roofline_outer"] = roof(main_res, "outer")
+    if full:
         out["also"] = {"config": {"workload": "llama1.1b x %d workers, H=%d, f16 pseudo-gradient"
-                                  % (args.k, args.h), "n_params": also["n_params"]},
+                                  % (args.k, args.h), "n_params": also["n_params"],
+                                  "note": "one warm-up round of 10 inner steps + 1 outer step; one "
+                                          "timed round; then 20 more timed outer steps"},
                        "value": also["round_GBps"], "ms_per_step": also["round_ms"],
                        "inner_step": also["inner"], "outer_step": also["outer"],
                        "roofline": roof(also, "inner"), "roofline_outer": roof(also, "outer"),
-                       "finite": also["finite"], "note": also["warmup_note"]}
-    if not args.no_also and args.workload == "llama150m":
-        out["mixed_precision"] = run_mixed_precision(4, 20, torch, D, synth)
-        pgr = run_workload("llama150m", args.k, 100, False, 1, 0, torch, D, synth, groups=True)
-        # worker-count sweep of the paper's ablation (1, 2, 4, 8 workers) and the
-        # reduced-precision pseudo-gradient modes, short timings on the 150M set
-        out["k_sweep"] = {"workload": "llama150m, FP32 pseudo-gradient, 40 inner + 20 outer launches",
-                          **{"k=%d" % kk: quick_measure("llama150m", kk, D.F32, 0, 40, 20, torch, D, synth)
-                             for kk in (1, 2, 4, 8)}}
-        out["pg_modes"] = {"workload": "llama150m x 8 workers, outer step only, 20 launches",
-                           **{nm: {kq: v for kq, v in quick_measure("llama150m", 8, pg, rm, 1, 20, torch, D,
-                                                                     synth).items() if kq.startswith("outer")}
-                              for nm, pg, rm in (("f32", D.F32, 0), ("f16", D.F16, 0),
-                                                 ("f16+rounded_mean", D.F16, 1), ("bf16", D.BF16, 0),
-                                                 ("bf16+rounded_mean", D.BF16, 1))}}
+                       "finite": also["finite"]}
+        # 50 more outer-step launches on the main workload's shape (the rounds above time only
+        # one per round)
+        out["outer_step_extra"] = B.quick("llama150m", args.k, pg=pg, n_inner=0, n_outer=50)["outer"]
+        out["placement_spread"] = {
+            "llama150m": B.placement_spread("llama150m", args.k, pg, 20, 20),
+            "llama1.1b": B.placement_spread("llama1.1b", args.k, D.F16, 10, 20)}
+        out["mixed_precision"] = B.mixed_precision(4, 20)
         out["param_groups"] = {
-            "config": {"workload": "llama150m x %d workers, 100 inner steps, 3 parameter groups "
-                                   "(norm vectors and embedding exempt from weight decay)" % args.k},
-            "inner_step": pgr["inner"]}
+            "config": {"workload": "llama150m and llama1.1b x %d workers, 3 parameter groups (norm "
+                                   "vectors and embeddings exempt from weight decay), 50 / 20 inner "
+                                   "launches" % args.k},
+            "llama150m": B.quick("llama150m", args.k, n_inner=50, n_outer=0, groups=True)["inner"],
+            "llama1.1b": B.quick("llama1.1b", args.k, n_inner=20, n_outer=0, groups=True)["inner"]}
+        # the paper's ablations: 1, 2, 4, 8 workers; H = 50, 125 (and 500 above); 4 workers at 1.1B
+        out["k_sweep"] = {"workload": "llama150m, FP32 pseudo-gradient, 30 inner + 20 outer launches",
+                          **{"k=%d" % kk: B.quick("llama150m", kk, n_inner=30, n_outer=20)
+                             for kk in (1, 2, 4, 8)}}
+        out["h_sweep"] = {"workload": "llama150m x %d workers, one timed round after a short warm-up "
+                                      "round" % args.k,
+                          **{"H=%d" % h: B.rounds("llama150m", args.k, h, pg, 1, 1, warmup_inner=5)
+                             for h in (50, 125)}}
+        out["llama1.1b_x4"] = dict(B.quick("llama1.1b", 4, pg=D.F16, n_inner=20, n_outer=20),
+                                   config="llama1.1b x 4 workers (the paper's 1.1B run), f16 "
+                                          "pseudo-gradient, 20 inner + 20 outer launches")
+        out["pg_modes"] = {"workload": "llama150m x %d workers, outer step only, 20 launches" % args.k,
+                           **{nm: B.quick("llama150m", args.k, pg=p, round_mean=rm, n_inner=0,
+                                          n_outer=20)["outer"]
+                              for nm, p, rm in (("f32", D.F32, 0), ("f16", D.F16, 0),
+                                                ("f16+rounded_mean", D.F16, 1), ("bf16", D.BF16, 0),
+                                                ("bf16+rounded_mean", D.BF16, 1))}}
+        out["outer_template_vs_runtime_k"] = {
+            "workload": "llama150m, FP32 pseudo-gradient, 20 outer launches; the kernel templated "
+                        "on k against the run-time-k kernel at the same k",
+            **{"k=%d" % kk: {"template": B.quick("llama150m", kk, n_inner=0, n_outer=20)["outer"],
+                             "runtime_k": B.quick("llama150m", kk, n_inner=0, n_outer=20,
+                                                  tune=dict(outer_anyk=1))["outer"]}
+               for kk in (4, 8)}}
+        out["tiny"] = dict(B.rounds("tiny", 2, 4, D.F32, 20, 2),
+                           note="0.79M parameters x 2 workers: cache-resident and launch-bound, "
+                                "reported for completeness, not roofline-meaningful")
     if not args.no_cpu:
         cb = cpu_baseline(args.k)
         n = main_res["n_params"]

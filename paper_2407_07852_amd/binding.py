@@ -187,17 +187,23 @@ class DiLoCo:
     exposes the flat buffers as tensor views of it, forwards the steps to the library."""
 
     def __init__(self, numel, k_workers, device="cuda:0", init_params=None, fill_theta0=None,
-                 **hyper):
+                 arena=None, **hyper):
         """init_params: list of FP32 device tensors packed into theta0; or fill_theta0: a
-        callable(theta0_view, layout, offsets) that writes the flat padded theta0 itself."""
+        callable(theta0_view, layout, offsets) that writes the flat padded theta0 itself.
+        arena: optional 1-D float32 device tensor to use as the arena (at least
+        layout.arena_bytes / 4 elements, 256-byte aligned) instead of a new allocation."""
         self.device = torch.device(device)
         self.k = k_workers
         cfg = make_config(numel, k_workers, **hyper)
         self.layout, self.offsets = diloco_query_layout(cfg)
         self.numel = [int(n) for n in numel]
         with torch.cuda.device(self.device):
-            self.arena = torch.empty(self.layout.arena_bytes // 4, dtype=torch.float32,
-                                     device=self.device)
+            if arena is None:
+                arena = torch.empty(self.layout.arena_bytes // 4, dtype=torch.float32,
+                                    device=self.device)
+            assert arena.dtype == torch.float32 and arena.is_contiguous() and arena.dim() == 1
+            assert arena.numel() * 4 >= self.layout.arena_bytes, "arena tensor too small"
+            self.arena = arena
             self.stream = torch.cuda.current_stream(self.device)
             cfg.arena = self.arena.data_ptr()
             cfg.arena_bytes = self.layout.arena_bytes
@@ -221,11 +227,21 @@ class DiLoCo:
         flat = self.arena[off_bytes // 4: off_bytes // 4 + (reps - 1) * L.stride + L.n_pad]
         return torch.as_strided(flat, (reps, L.n_pad), (L.stride, 1))
 
-    def new_grads(self, dtype=torch.float32):
+    def grads_numel(self):
+        """Elements of a gradient buffer whose replicas are spaced like the arena's."""
+        return (self.k - 1) * self.layout.stride + self.layout.n_pad
+
+    def new_grads(self, dtype=torch.float32, out=None):
         """A zeroed gradient buffer [k][n_pad] of the given dtype, replicas spaced like the
-        arena's (stride elements apart) so that all streams of a tile share their alignment."""
+        arena's (stride elements apart) so that all streams of a tile share their alignment.
+        out: optional 1-D device tensor of that dtype with at least grads_numel() elements to
+        use instead of a new allocation."""
         L = self.layout
-        flat = torch.zeros((self.k - 1) * L.stride + L.n_pad, dtype=dtype, device=self.device)
+        if out is None:
+            flat = torch.zeros(self.grads_numel(), dtype=dtype, device=self.device)
+        else:
+            assert out.dtype == dtype and out.numel() >= self.grads_numel()
+            flat = out[:self.grads_numel()].zero_()
         return torch.as_strided(flat, (self.k, L.n_pad), (L.stride, 1))
 
     def new_flags(self):

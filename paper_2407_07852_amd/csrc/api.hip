@@ -518,7 +518,7 @@ int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value) {
   const std::string n(name);
   const bool block_ok = value == 64 || value == 128 || value == 256;
   if (n == "inner_block" && block_ok) t.inner_block = value;
-  else if (n == "outer_block" && block_ok) t.outer_block = value;
+  else if (n == "outer_block" && (block_ok || value == -1)) t.outer_block = value;
   else if (n == "inner_waves" && value >= -1 && value <= 32) t.inner_waves = value;
   else if (n == "outer_waves" && value >= -1 && value <= 32) t.outer_waves = value;
   else if (n == "outer_anyk" && (value == 0 || value == 1)) t.outer_anyk = value;

@@ -29,7 +29,7 @@ struct StepEntry {
 struct Tuning {
   int inner_block = 64;   // threads per workgroup (64, 128 or 256), one 128-bit vector per lane
   int inner_waves = -1;   // resident waves per CU: -1 = auto, 0 = hardware maximum
-  int outer_block = 128;  // threads per workgroup of the outer step (64, 128 or 256)
+  int outer_block = -1;   // threads per workgroup of the outer step (64, 128 or 256): -1 = auto
   int outer_waves = -1;   // resident waves per CU for the outer step: -1 = auto, 0 = maximum
   int outer_anyk = 0;     // 1: use the run-time-k kernel for every k (comparison with the templates)
   int check_block = 256;  // 64 or 256

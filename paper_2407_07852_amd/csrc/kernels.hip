@@ -239,10 +239,12 @@ __global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint3
   if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
-// Any k (run-time loop over the workers).
+// Any k (run-time loop over the workers), in batches of up to 16 workers whose loads are all in
+// flight together; the sum still runs over the workers in ascending order.
 template <int PG, bool RM, int B>
 __global__ __launch_bounds__(B) void outer_fused_anyk_kernel(const OuterArgs a, uint32_t tiles) {
   constexpr bool NT = true;
+  constexpr int kBatch = 16;
   f32x4* __restrict__ t0_p = reinterpret_cast<f32x4*>(a.theta0);
   f32x4* __restrict__ b_p = reinterpret_cast<f32x4*>(a.mom);
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(a.theta);
@@ -250,17 +252,23 @@ __global__ __launch_bounds__(B) void outer_fused_anyk_kernel(const OuterArgs a, 
   const size_t i = (size_t)blockIdx.x * B + threadIdx.x;
   f32x4 t0 = ld<NT>(t0_p + i);
   f32x4 b = ld<NT>(b_p + i);
-  f32x4 s;
-  {
-    const f32x4 th = ld<NT>(th_p + i);
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  for (int r0 = 0; r0 < a.k; r0 += kBatch) {
+    f32x4 th[kBatch];
 #pragma unroll
-    for (int c = 0; c < kVecElems; ++c) s[c] = pseudo_grad<PG>(t0[c], th[c]);
-  }
-#pragma unroll 4
-  for (int r = 1; r < a.k; ++r) {
-    const f32x4 th = ld<NT>(th_p + (size_t)r * rstride + i);
+    for (int j = 0; j < kBatch; ++j)
+      if (r0 + j < a.k) th[j] = ld<NT>(th_p + (size_t)(r0 + j) * rstride + i);
 #pragma unroll
-    for (int c = 0; c < kVecElems; ++c) s[c] = s[c] + pseudo_grad<PG>(t0[c], th[c]);
+    for (int j = 0; j < kBatch; ++j) {
+      if (r0 + j < a.k) {
+#pragma unroll
+        for (int c = 0; c < kVecElems; ++c) {
+          const float d = pseudo_grad<PG>(t0[c], th[j][c]);
+          // the first worker's pseudo-gradient starts the sum (0 + d would lose the sign of -0)
+          s[c] = (j == 0 && r0 == 0) ? d : s[c] + d;
+        }
+      }
+    }
   }
   const bool pow2 = (a.k & (a.k - 1)) == 0;
 #pragma unroll
@@ -449,21 +457,29 @@ hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const 
   return g16 ? launch_inner_b<true, false>(a, k, t, s) : launch_inner_b<false, false>(a, k, t, s);
 }
 
-// Resident waves per CU of the outer step.  With only ~4 waves resident (k >= 7) the conversions
-// of the reduced-precision modes lengthen each wave's compute phase enough to under-fill the
-// memory pipe: two more waves measured +0.5...0.9 % there (k = 8), and -2 % at smaller k, where
-// more waves are resident anyway.
-static int outer_waves(const Tuning& t, int k, int pg) {
-  if (t.outer_waves >= 0) return t.outer_waves;
-  int waves = auto_waves_outer(k);
-  if (pg != 0 && waves <= 4) waves += 2;
-  return waves;
+// Launch shape of the outer step: threads per workgroup and resident waves per CU, by k and
+// pseudo-gradient type.  Measured optima on MI355X at the 150M and the 1.1B set (medians of 12-20
+// launches; the best shape is the same at both sizes): with few streams (k <= 2) two-wave
+// workgroups, which put 2 KiB of every stream in flight from one CU at the same moment, gain 1-2
+// points; from k = 3 on single-wave workgroups are as fast or faster and never fall off a cliff
+// (two-wave workgroups lose 5-15 points at some k / type combinations).  The reduced-precision
+// modes' conversions lengthen each wave's compute phase, which at k = 4, 5 wants one more wave.
+struct OuterShape { int block, waves; };
+static OuterShape outer_shape(const Tuning& t, int k, int pg) {
+  static const int kWaves32[9] = {0, 12, 10, 7, 5, 5, 5, 6, 5};
+  static const int kWaves16[9] = {0, 12, 10, 7, 6, 6, 5, 6, 5};
+  OuterShape s;
+  s.block = t.outer_block > 0 ? t.outer_block : (k <= 2 ? 128 : 64);
+  if (t.outer_waves >= 0) s.waves = t.outer_waves;
+  else if (k <= 8) s.waves = pg != 0 ? kWaves16[k] : kWaves32[k];
+  else s.waves = auto_waves_outer(k > 16 ? 16 : k);  // 16 workers' loads per batch
+  return s;
 }
 
 template <int K, int PG, bool RM, int B>
 static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
-  const uint32_t lds = pad_lds_bytes(outer_waves(t, K, PG), B, t.lds_per_cu);
+  const uint32_t lds = pad_lds_bytes(outer_shape(t, K, PG).waves, B, t.lds_per_cu);
   hipLaunchKernelGGL((outer_fused_kernel<K, PG, RM, B>), dim3((uint32_t)tiles), dim3(B), lds, s, a,
                      (uint32_t)tiles);
   return hipGetLastError();
@@ -485,7 +501,7 @@ static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, hipStream_
     }
   }
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
-  const uint32_t lds = pad_lds_bytes(outer_waves(t, a.k, PG), B, t.lds_per_cu);
+  const uint32_t lds = pad_lds_bytes(outer_shape(t, a.k, PG).waves, B, t.lds_per_cu);
   hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM, B>), dim3((uint32_t)tiles), dim3(B), lds, s,
                      a, (uint32_t)tiles);
   return hipGetLastError();
@@ -493,10 +509,10 @@ static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, hipStream_
 
 template <int PG, bool RM>
 static hipError_t launch_outer_b(const OuterArgs& a, const Tuning& t, hipStream_t s) {
-  switch (t.outer_block) {
-    case 64: return launch_outer_k<PG, RM, 64>(a, t, s);
+  switch (outer_shape(t, a.k, PG).block) {
+    case 128: return launch_outer_k<PG, RM, 128>(a, t, s);
     case 256: return launch_outer_k<PG, RM, 256>(a, t, s);
-    default: return launch_outer_k<PG, RM, 128>(a, t, s);
+    default: return launch_outer_k<PG, RM, 64>(a, t, s);
   }
 }
 
