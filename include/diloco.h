@@ -17,12 +17,15 @@
  *
  * theta0 = outer weights theta(t); mom = outer momentum buffer; theta/m/v = each worker's
  * weights and AdamW moments.  Every tensor of the parameter list starts at a multiple of 64
- * elements inside each buffer; the gaps and the tail up to n_pad hold zeros and stay zero.
+ * elements inside each buffer; the gaps and the tail up to n_pad hold zeros, and stay zero as
+ * long as the gradient buffers hold zeros there too (both steps map 0 to 0).
  *
  * Conventions
  *   - "device" pointers are GPU global memory; "host" pointers are ordinary process memory.
  *   - The caller owns every large allocation (arena, gradients, flags).  The library borrows
- *     them; it allocates only O(k) bytes of device state of its own.
+ *     them.  Of its own it allocates 40*k bytes of device memory at diloco_init (per-worker
+ *     step state and the per-step table) and, only if diloco_set_param_groups is used,
+ *     n_pad/64 bytes more; the other entry points allocate nothing.
  *   - Every call returns DILOCO_OK (0), a positive informational code, or a negative error.
  *     On an error nothing has been launched.  No exception or abort crosses this boundary.
  *   - All device work is enqueued asynchronously on the stream given at init.
@@ -103,40 +106,57 @@ typedef struct {
   uint64_t off_theta0, off_mom, off_theta, off_m, off_v; /* byte offsets inside the arena */
 } diloco_layout;
 
-/* Flat layout for cfg's tensor list and k (host only, touches no GPU).  tensor_offsets may be
- * NULL; otherwise it receives n_tensors element offsets, valid inside every flat buffer (and
- * inside the caller's gradient buffers). */
+/* Flat layout for cfg's tensor list and k (host only, touches no GPU): the per-tensor iteration
+ * of Figure 1 (`for param in model.parameters()`) becomes one pass over flat buffers; the two
+ * model copies of paragraph "General Implementation Details" are theta0 and theta.
+ * tensor_offsets may be NULL; otherwise it receives n_tensors element offsets, valid inside
+ * every flat buffer (and inside the caller's gradient buffers).
+ * Errors: DILOCO_ERR_INVALID_ARG (NULL, no tensors, an empty tensor, k out of range, more than
+ * 2^33 parameters). */
 int diloco_query_layout(const diloco_config* cfg, diloco_layout* out, uint64_t* tensor_offsets);
 
 /* Creates a context over cfg->arena.  init_params: host array of n_tensors DEVICE pointers to
  * FP32 tensors that are packed into theta0; or NULL when theta0 in the arena already holds the
- * flat padded weights.  Then (Figure 1's starting state) every worker's weights are set to
- * theta0, moments and the outer momentum buffer to zero, step counts to zero; pads are zeroed.
- * *out is set only on success. */
+ * flat padded weights.  Then (Figure 1's starting state: every worker starts from the same
+ * weights, `original_params` is a copy of them) every worker's weights are set to theta0,
+ * moments and the outer momentum buffer to zero, step counts to zero; pads are zeroed.
+ * *out is set only on success.  Errors: DILOCO_ERR_INVALID_ARG (problem or hyper-parameters out
+ * of range, a pointer that is not memory of the current device or does not fit its
+ * allocation), DILOCO_ERR_ALIGN, DILOCO_ERR_ARENA_TOO_SMALL, DILOCO_ERR_HIP. */
 int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco_ctx** out);
 
-/* Gradient-scaler support for the inner step (mixed precision; Section "Implementation").
- * grads: device, [k][grad_stride] elements of grad_dtype, laid out like the flat buffers
- * (pads must be zero or at least finite).  Sets found_inf[r] (device, k int32) to 1 if any
- * element of worker r's gradient is +-inf or NaN, else 0, and records inv_scale (finite, > 0)
- * as the factor the next diloco_inner_step applies to these gradients.  The gradients are
- * not modified: the multiply is fused into the inner step. */
+/* Gradient-scaler support for the inner step (mixed precision; Section "Implementation",
+ * paragraph "General Implementation Details": the scaler acts in the inner step only).
+ * grads: device, [k][grad_stride] elements of grad_dtype (DILOCO_F32 or DILOCO_F16), laid out
+ * like the flat buffers; the pads must hold zeros (a non-finite pad would raise the flag, a
+ * non-zero finite pad would move the pads of theta, m and v away from zero).  Sets found_inf[r]
+ * (device, k int32) to 1 if any element of worker r's gradient is +-inf or NaN, else 0, and
+ * records inv_scale (finite, > 0) as the factor the next diloco_inner_step applies to these
+ * gradients, whatever their type.  The gradients are not modified: the multiply is fused into
+ * the inner step.  Enqueues two kernels (flag clearing, check) and no memset.
+ * Errors: DILOCO_ERR_INVALID_ARG, DILOCO_ERR_ALIGN, DILOCO_ERR_HIP. */
 int diloco_unscale_check(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
                          int32_t grad_dtype, float inv_scale, int32_t* found_inf);
 
-/* One AdamW step of all k workers in one launch:
+/* The inner optimizer step of Section "Implementation" (AdamW; `inner_optimizer.step()` in
+ * Figure 1) for all k workers at once:
  *   g = grad (* inv_scale when found_inf is given)
  *   m = beta1*m + (1-beta1)*g ;  v = beta2*v + (1-beta2)*g*g
  *   theta = theta - lr*wd*theta - lr * (m/(1-beta1^t)) / (sqrt(v/(1-beta2^t)) + eps)
  * with t the worker's own step count.  grads as in diloco_unscale_check (grad_stride >= n_pad,
  * a multiple of 8 elements; base 16-byte aligned).  lr < 0 selects cfg->inner_lr.
- * found_inf: NULL, or the device flags written by the preceding diloco_unscale_check (else
- * DILOCO_ERR_STATE); a worker whose flag is set skips the step: its weights, moments and step
- * count stay untouched.  Returns DILOCO_ROUND_COMPLETE on every H-th call since the last outer
- * step.
- * Stream capture: the call enqueues exactly one kernel and no memset; the per-worker step state
- * alternates between two device slots from call to call, so a captured HIP graph must hold an
- * even number of inner steps to be replayable. */
+ * found_inf: NULL, or the device flags written by the preceding diloco_unscale_check of the
+ * same gradient buffer (else DILOCO_ERR_STATE); a worker whose flag is set skips the step: its
+ * weights, moments and step count stay untouched.  DILOCO_F16 gradients exist only under a loss
+ * scale, so they REQUIRE found_inf (DILOCO_ERR_STATE without it: they are never stepped
+ * unchecked and unscaled).  Returns DILOCO_ROUND_COMPLETE on every H-th call since the last
+ * outer step (a host-side count of calls: replays of a captured graph are not counted).
+ * Stream capture: the call enqueues exactly two kernels and no memset -- a one-wave prologue that
+ * advances every worker's step count and running beta^t products in place on the device (or
+ * marks the worker inactive) and the AdamW kernel that reads the prologue's table.  The step
+ * state lives on the device only, so a captured sequence with any number of inner steps, odd
+ * included, replays correctly and can be mixed with eager calls.
+ * Errors: DILOCO_ERR_INVALID_ARG, DILOCO_ERR_ALIGN, DILOCO_ERR_STATE, DILOCO_ERR_HIP. */
 int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
                       int32_t grad_dtype, double lr, const int32_t* found_inf);
 
@@ -162,34 +182,46 @@ int diloco_set_param_groups(diloco_ctx* ctx, const uint8_t* group_of_tensor, uin
 double diloco_lr_at(uint64_t step, uint64_t warmup_steps, uint64_t total_steps, double base_lr,
                     double final_ratio);
 
-/* The outer step of Figure 1, fused into one launch:
+/* The outer step of Figure 1 (pseudo-gradient, `all_reduce(op=AVG)` over the workers, reset,
+ * `outer_optimizer.step()` = SGD with Nesterov momentum, re-snapshot; hyper-parameters of
+ * Appendix A, Table 3; reduced-precision variant of Section "All-Reduce in FP16"), fused into
+ * one launch:
  *   delta_r = theta0 - theta_r            (optionally rounded through binary16 / bfloat16)
  *   dbar    = (delta_0 + ... + delta_{k-1}) / k        (FP32, workers in ascending order;
  *                                                       rounded too when pg_round_mean is set)
  *   mom     = mu*mom + dbar ;  theta0 = theta0 - outer_lr*(dbar + mu*mom)
  *   theta_r = theta0 for every r.
  * AdamW moments and step counts are not touched.  Legal after any number of inner steps,
- * including none.  The gradient scaler plays no part here. */
+ * including none.  The gradient scaler plays no part here, and non-finite pseudo-gradients
+ * propagate as IEEE arithmetic dictates.  Enqueues one kernel.  Errors: DILOCO_ERR_HIP. */
 int diloco_outer_step(diloco_ctx* ctx);
 
-/* Device address of a flat buffer (replica ignored for THETA0 / MOM). */
+/* Device address of a flat buffer (replica ignored for THETA0 / MOM): the two model copies and
+ * the optimizer states of paragraph "General Implementation Details", e.g. to view a worker's
+ * parameter tensors in place at tensor_offsets.  Errors: DILOCO_ERR_INVALID_ARG. */
 int diloco_get_buffer(diloco_ctx* ctx, int which, uint32_t replica, void** dev_ptr);
 
-/* The layout this context was created with (same values as diloco_query_layout). */
+/* The layout this context was created with (same values as diloco_query_layout).
+ * Errors: DILOCO_ERR_INVALID_ARG (NULL). */
 int diloco_get_layout(diloco_ctx* ctx, diloco_layout* out);
 
-/* Per-worker AdamW step counts t_r into the host array steps[k].  Synchronises the stream. */
+/* Per-worker AdamW step counts t_r into the host array steps[k]: a worker's count advances only
+ * when its step is taken (a step skipped by the scaler is an optimizer step that was not
+ * called; "General Implementation Details").  Synchronises the stream.
+ * Errors: DILOCO_ERR_INVALID_ARG, DILOCO_ERR_HIP. */
 int diloco_get_steps(diloco_ctx* ctx, uint32_t* steps);
 
-/* The pseudo-gradient's FP32 -> binary16 rounding on its own, as the outer step applies it
- * (Section "All-Reduce in FP16"): in/out are device arrays of n elements (out: uint16 codes). */
+/* DIAGNOSTIC, not part of the training path: the pseudo-gradient's FP32 -> binary16 / bfloat16
+ * rounding on its own, with the same hardware conversion the outer step applies (Section
+ * "All-Reduce in FP16"): in/out are device arrays of n elements (out: uint16 codes). */
 int diloco_cast_f32_to_f16(const float* in, uint16_t* out, uint64_t n, void* stream);
 int diloco_cast_f32_to_bf16(const float* in, uint16_t* out, uint64_t n, void* stream);
 
-/* Launch-shape knobs for benchmarking sweeps; results never depend on them.  Names and values:
- *   inner_block 64|256, inner_vec 1|4 (threads per workgroup, 128-bit vectors per lane and stream),
- *   inner_nt 0|1 (nontemporal accesses), xcd_remap 0|1 (inner step: contiguous tile range per XCD),
+/* DIAGNOSTIC: launch-shape knobs for benchmarking sweeps; results never depend on them.  Names
+ * and values:
+ *   inner_block 64|128|256, outer_block -1|64|128|256 (threads per workgroup; -1 automatic),
  *   inner_waves / outer_waves -1..32 (resident waves per CU: -1 automatic, 0 hardware maximum),
+ *   outer_anyk 0|1 (1: the run-time-k kernel also for k <= 8),
  *   check_block 64|256, check_vec 1|2|4|8, check_waves 0..32, check_persist 0..64.
  * The defaults are the measured optimum on MI355X.  Unknown names or values return
  * DILOCO_ERR_INVALID_ARG. */
