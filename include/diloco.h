@@ -160,6 +160,52 @@ int diloco_unscale_check(diloco_ctx* ctx, const void* grads, uint64_t grad_strid
 int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
                       int32_t grad_dtype, double lr, const int32_t* found_inf);
 
+/* Per-worker AdamW step state as diloco_inner_step_noalloc keeps it in caller memory: the running
+ * products beta1^t and beta2^t and the step count t.  A fresh worker is {1.0, 1.0, 0, 0}. */
+typedef struct {
+  double beta1_pow;
+  double beta2_pow;
+  int32_t step;
+  int32_t reserved; /* 0 */
+} diloco_step_state;
+
+/* Arguments of diloco_inner_step_noalloc.  All pointers are DEVICE pointers owned by the caller;
+ * the struct itself is host memory, read during the call only. */
+typedef struct {
+  float* theta;                  /* worker 0's weights; worker r at + r*stride; in/out */
+  float* m;                      /* AdamW first moments, same spacing; in/out */
+  float* v;                      /* AdamW second moments, same spacing; in/out */
+  uint64_t stride;               /* elements between workers, >= n_pad, multiple of 4 */
+  uint64_t n_pad;                /* elements per worker, a positive multiple of DILOCO_TILE */
+  uint32_t k_workers;            /* 1 .. DILOCO_MAX_WORKERS */
+  int32_t grad_dtype;            /* DILOCO_F32 or DILOCO_F16 */
+  const void* grads;             /* [k][grad_stride] gradients, 16-byte aligned */
+  uint64_t grad_stride;          /* >= n_pad, multiple of 8 */
+  float inv_scale;               /* factor applied to every gradient element (1.0 = none) */
+  const int32_t* found_inf;      /* k flags, or NULL; a flagged worker takes no step */
+  diloco_step_state* step_state; /* [k], in/out, 8-byte aligned */
+  double lr, beta1, beta2, eps, weight_decay;
+  void* stream;                  /* hipStream_t; NULL = the default stream */
+} diloco_inner_call;
+
+/* diloco_inner_step for callers that cannot allocate device memory at all -- code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc -- and therefore cannot
+ * create a context either (diloco_init allocates the step state and the per-step table).  Same
+ * kernels, same arithmetic and same results as diloco_inner_step with a single parameter
+ * group; the caller passes every input and output explicitly, including the per-worker step
+ * state, and the per-step table that the prologue kernel writes for the AdamW kernel lives in a
+ * static device array inside the library (1 KiB per GPU, DILOCO_MAX_WORKERS entries).
+ * The call allocates nothing, on the device or on the host, and enqueues two kernels on
+ * `stream` of the current device.  k_workers above DILOCO_MAX_WORKERS is rejected with
+ * DILOCO_ERR_INVALID_ARG.  All calls on one GPU share the one static table: calls whose kernels
+ * may overlap on the same GPU (different streams, different threads) race and must be
+ * serialised by the caller; nothing needs clearing between calls, each call overwrites the
+ * entries it reads.  Pointer extents are NOT checked against their allocations (that would cost
+ * runtime queries); NULL, alignment, sizes and hyper-parameter ranges are.
+ * Errors: DILOCO_ERR_INVALID_ARG, DILOCO_ERR_ALIGN, DILOCO_ERR_STATE (DILOCO_F16 gradients
+ * without found_inf), DILOCO_ERR_HIP; message via diloco_last_error(NULL). */
+int diloco_inner_step_noalloc(const diloco_inner_call* call);
+
 /* Per-tensor parameter groups for the inner optimizer: the paper prints one weight decay (0.1)
  * and one learning rate with 1000 warm-up steps (Appendix A, Table 3); training codes built on
  * the paper's framework commonly exempt norm and embedding tensors from decay, which is what

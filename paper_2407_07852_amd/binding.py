@@ -20,7 +20,8 @@ MAX_WORKERS, TENSOR_ALIGN, TILE, MAX_GROUPS = 64, 64, 8192, 8
 EXPORTS = ["diloco_query_layout", "diloco_init", "diloco_unscale_check", "diloco_inner_step",
            "diloco_outer_step", "diloco_get_buffer", "diloco_get_layout", "diloco_get_steps",
            "diloco_cast_f32_to_f16", "diloco_set_tuning", "diloco_last_error", "diloco_destroy",
-           "diloco_set_param_groups", "diloco_lr_at", "diloco_cast_f32_to_bf16"]
+           "diloco_set_param_groups", "diloco_lr_at", "diloco_cast_f32_to_bf16",
+           "diloco_inner_step_noalloc"]
 
 
 class Config(C.Structure):
@@ -36,6 +37,19 @@ class Config(C.Structure):
 class Layout(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("n_pad", "stride", "arena_bytes", "off_theta0",
                                           "off_mom", "off_theta", "off_m", "off_v")]
+
+
+class InnerCall(C.Structure):
+    """diloco_inner_call: every pointer a device address."""
+    _fields_ = [("theta", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
+                ("stride", C.c_uint64), ("n_pad", C.c_uint64), ("k_workers", C.c_uint32),
+                ("grad_dtype", C.c_int32), ("grads", C.c_void_p), ("grad_stride", C.c_uint64),
+                ("inv_scale", C.c_float), ("found_inf", C.c_void_p), ("step_state", C.c_void_p),
+                ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
+                ("eps", C.c_double), ("weight_decay", C.c_double), ("stream", C.c_void_p)]
+
+
+STEP_STATE_BYTES = 24  # diloco_step_state: two doubles, two int32
 
 
 class DilocoError(RuntimeError):
@@ -72,6 +86,7 @@ def lib():
         L.diloco_set_param_groups.argtypes = [vp, C.POINTER(C.c_uint8), u32,
                                               C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.diloco_lr_at.argtypes = [u64, u64, u64, C.c_double, C.c_double]
+        L.diloco_inner_step_noalloc.argtypes = [C.POINTER(InnerCall)]
         for n in EXPORTS:
             if n not in ("diloco_last_error", "diloco_lr_at"):
                 getattr(L, n).restype = C.c_int
@@ -172,6 +187,13 @@ def diloco_set_param_groups(ctx, group_of_tensor, lr_scale, weight_decay):
 
 def diloco_lr_at(step, warmup_steps, total_steps, base_lr, final_ratio=1.0):
     return lib().diloco_lr_at(step, warmup_steps, total_steps, base_lr, final_ratio)
+
+
+def diloco_inner_step_noalloc(**fields):
+    """Fields of diloco_inner_call by name (device addresses as ints); allocates nothing on the
+    device."""
+    call = InnerCall(**fields)
+    return _check(lib().diloco_inner_step_noalloc(C.byref(call)))
 
 
 def diloco_last_error(ctx=None):

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -41,16 +42,16 @@ struct diloco_ctx {
 
 namespace {
 
-thread_local std::string g_err;
+// Last error of the calling thread for calls without a context: a fixed buffer, so that
+// reporting an error never allocates.
+thread_local char g_err[512] = "";
 
 int fail(diloco_ctx* ctx, int code, const char* fmt, ...) {
-  char buf[512];
   va_list ap;
   va_start(ap, fmt);
-  vsnprintf(buf, sizeof buf, fmt, ap);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
   va_end(ap);
-  if (ctx) ctx->err = buf;
-  g_err = buf;
+  if (ctx) ctx->err = g_err;
   return code;
 }
 
@@ -189,6 +190,47 @@ int check_grads(diloco_ctx* ctx, const void* grads, uint64_t grad_stride, int32_
   return rc;
 }
 
+// ---- scratch of the entry point that allocates nothing ---------------------------------------
+// The per-step table of diloco_inner_step_noalloc: one StepEntry per worker, written by the step
+// prologue kernel and read by the AdamW kernel of the same call.  Every GPU the library runs on
+// holds its own copy of this array until the process ends.  In host code the array's name is
+// only a stand-in; the device address comes from hipGetSymbolAddress, once per device.
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[DILOCO_MAX_WORKERS * sizeof(StepEntry)];
+static void* g_scratch_ptr[kMaxDevices];  // per device, resolved with that device current
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (resolved on first use); *dev receives the
+// device id.  Returns a HIP error code.
+hipError_t scratch_on_current_device(void** ptr, int* dev) {
+  hipError_t e = hipGetDevice(dev);
+  if (e != hipSuccess) return e;
+  if (*dev < 0 || *dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[*dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[*dev] = p;
+  }
+  *ptr = g_scratch_ptr[*dev];
+  return hipSuccess;
+}
+
+// The AdamW kernel's scalar arguments: each is formed in double and rounded to float once.
+void fill_inner_scalars(InnerArgs& a, double lr, double beta1, double beta2, double eps,
+                        double weight_decay, float inv_scale) {
+  a.beta1 = (float)beta1;
+  a.beta2 = (float)beta2;
+  a.omb1 = (float)(1.0 - beta1);
+  a.omb2 = (float)(1.0 - beta2);
+  a.lr = (float)lr;
+  a.lr_wd = (float)(lr * weight_decay);
+  a.eps = (float)eps;
+  a.inv_scale = inv_scale;
+}
+
 }  // namespace
 
 extern "C" {
@@ -234,8 +276,7 @@ int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco
   auto bail = [&](int code) {
     if (c->d_state) (void)hipFree(c->d_state);
     if (c->d_chunk_group) (void)hipFree(c->d_chunk_group);
-    g_err = c->err.empty() ? g_err : c->err;
-    delete c;
+    delete c;  // the message stays in the thread's buffer
     return code;
   };
 
@@ -255,6 +296,14 @@ int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco
 
   rc = check_device_range(c, c->device, cfg->arena, c->lay.arena_bytes, "arena");
   if (rc != DILOCO_OK) return bail(rc);
+  {
+    // set-up is also where the static step table of diloco_inner_step_noalloc gets its device
+    // address on this GPU, so that the first such call has nothing left to resolve
+    void* table = nullptr;
+    int dev = -1;
+    e = scratch_on_current_device(&table, &dev);
+    if (e != hipSuccess) return bail(fail_hip(c, "address of the static step table", e));
+  }
 
   const uint32_t k = cfg->k_workers;
   // One allocation: the step state [k], then the per-step table [k].
@@ -348,15 +397,7 @@ int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
   a.g_stride = grad_stride;
   a.n_pad = ctx->lay.n_pad;
   a.table = ctx->d_table;
-  // Each scalar is formed in double and rounded to float once.
-  a.beta1 = (float)cf.beta1;
-  a.beta2 = (float)cf.beta2;
-  a.omb1 = (float)(1.0 - cf.beta1);
-  a.omb2 = (float)(1.0 - cf.beta2);
-  a.lr = (float)lr;
-  a.lr_wd = (float)(lr * cf.weight_decay);
-  a.eps = (float)cf.eps;
-  a.inv_scale = inv_scale;
+  fill_inner_scalars(a, lr, cf.beta1, cf.beta2, cf.eps, cf.weight_decay, inv_scale);
   a.chunk_group = ctx->d_chunk_group;
   for (uint32_t q = 0; q < DILOCO_MAX_GROUPS; ++q) {
     const bool used = q < ctx->n_groups;
@@ -373,6 +414,64 @@ int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
   ctx->steps_since_outer += 1;
   if (cf.h_inner_steps != 0 && ctx->steps_since_outer % cf.h_inner_steps == 0)
     return DILOCO_ROUND_COMPLETE;
+  return DILOCO_OK;
+}
+
+int diloco_inner_step_noalloc(const diloco_inner_call* c) {
+  if (!c) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "call is NULL");
+  if (!c->theta || !c->m || !c->v || !c->grads || !c->step_state)
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "NULL buffer in diloco_inner_call");
+  if (c->k_workers == 0 || c->k_workers > DILOCO_MAX_WORKERS)
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG,
+                "k_workers %u is outside 1..%d, the size of the library's static step table",
+                c->k_workers, DILOCO_MAX_WORKERS);
+  if (c->n_pad == 0 || c->n_pad % DILOCO_TILE != 0 || c->n_pad > (1ull << 33))
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG,
+                "n_pad must be a positive multiple of %u elements, at most 2^33", DILOCO_TILE);
+  if (c->stride < c->n_pad || c->grad_stride < c->n_pad)
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "stride and grad_stride must be at least n_pad");
+  if (c->grad_dtype != DILOCO_F32 && c->grad_dtype != DILOCO_F16)
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "unknown grad_dtype %d", c->grad_dtype);
+  if ((((uintptr_t)c->theta | (uintptr_t)c->m | (uintptr_t)c->v | (uintptr_t)c->grads) & 15u) != 0 ||
+      (c->stride & 3u) != 0 || (c->grad_stride & 7u) != 0 || ((uintptr_t)c->step_state & 7u) != 0 ||
+      ((uintptr_t)c->found_inf & 3u) != 0)
+    return fail(nullptr, DILOCO_ERR_ALIGN,
+                "buffers must be 16-byte aligned, stride a multiple of 4 and grad_stride of 8 elements");
+  if (!finite_in(c->lr, 0, false, HUGE_VAL, true) || !finite_in(c->beta1, 0, false, 1, true) ||
+      !finite_in(c->beta2, 0, false, 1, true) || !finite_in(c->eps, 0, true, HUGE_VAL, true) ||
+      !finite_in(c->weight_decay, 0, false, HUGE_VAL, true))
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "hyper-parameter out of range");
+  if (!std::isfinite(c->inv_scale) || !(c->inv_scale > 0.0f))
+    return fail(nullptr, DILOCO_ERR_INVALID_ARG, "inv_scale must be finite and > 0");
+  if (c->grad_dtype == DILOCO_F16 && !c->found_inf)
+    return fail(nullptr, DILOCO_ERR_STATE, "binary16 gradients need found_inf flags of a check");
+
+  void* table = nullptr;
+  int dev = -1;
+  hipError_t e = scratch_on_current_device(&table, &dev);
+  if (e != hipSuccess) return fail_hip(nullptr, "address of the static step table", e);
+
+  InnerArgs a;
+  a.theta = c->theta;
+  a.m = c->m;
+  a.v = c->v;
+  a.g = c->grads;
+  a.stride = c->stride;
+  a.g_stride = c->grad_stride;
+  a.n_pad = c->n_pad;
+  a.table = static_cast<const StepEntry*>(table);
+  fill_inner_scalars(a, c->lr, c->beta1, c->beta2, c->eps, c->weight_decay, c->inv_scale);
+  a.chunk_group = nullptr;
+  for (uint32_t q = 0; q < DILOCO_MAX_GROUPS; ++q) a.lr_g[q] = a.lr_wd_g[q] = 0.0f;
+  const hipStream_t stream = (hipStream_t)c->stream;
+  // The prologue overwrites the first k entries of the table, which is all the AdamW kernel of
+  // this call reads: nothing of an earlier call's contents is used.
+  e = launch_prologue(reinterpret_cast<RepState*>(c->step_state), static_cast<StepEntry*>(table),
+                      c->found_inf, c->beta1, c->beta2, (int)c->k_workers, stream);
+  if (e != hipSuccess) return fail_hip(nullptr, "step prologue launch", e);
+  Tuning tune;  // defaults; the LDS size of gfx950 CUs is the struct's default
+  e = launch_inner(a, (int)c->k_workers, c->grad_dtype == DILOCO_F16, false, tune, stream);
+  if (e != hipSuccess) return fail_hip(nullptr, "inner step launch", e);
   return DILOCO_OK;
 }
 
@@ -532,7 +631,7 @@ int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value) {
 
 const char* diloco_last_error(diloco_ctx* ctx) {
   if (ctx) return ctx->err.c_str();
-  return g_err.c_str();
+  return g_err;
 }
 
 int diloco_destroy(diloco_ctx* ctx) {
