@@ -44,6 +44,10 @@ def lib():
             "oracle_nesterov_step_f32": (None, [vp, vp, vp, sz, f64, f64]),
             "oracle_nesterov_step_f64": (None, [vp, vp, vp, sz, f64, f64]),
             "oracle_outer_step_f32": (None, [vp, vp, vp, sz, sz, f64, f64, i32, i32, vp, vp]),
+            "oracle_outer_update_from_snapshot_f32": (None, [vp, vp, vp, sz, sz, f64, f64, i32, i32,
+                                                             vp, vp]),
+            "oracle_merge_delayed_f32": (None, [vp, vp, vp, sz, sz]),
+            "oracle_merge_delayed_f64": (None, [vp, vp, vp, sz, sz]),
             "oracle_f32_to_bf16_rne": (u16, [f32]),
             "oracle_bf16_to_f32": (f32, [u16]),
             "oracle_cast_f32_to_bf16": (None, [vp, vp, sz]),
@@ -241,6 +245,27 @@ def outer_step(theta0, b, theta, outer_lr, mu, pg_f16, scratch=None, round_mean=
     return mean
 
 
+# ---- delayed application of the outer step --------------------------------------
+def outer_update_from_snapshot(theta0, b, snap, outer_lr, mu, pg=False, round_mean=False):
+    """Outer update computed from the workers' snapshotted weights snap [k][n]: theta0 and b
+    are updated in place, no worker is reset.  float32."""
+    k, n = snap.shape
+    d = np.empty((k, n), dtype=np.float32)
+    mean = np.empty(n, dtype=np.float32)
+    lib().oracle_outer_update_from_snapshot_f32(
+        _p(theta0, np.float32), _p(b, np.float32), _p(snap, np.float32), k, n, outer_lr, mu,
+        _pg_code(pg), 1 if round_mean else 0, _p(d, np.float32), _p(mean, np.float32))
+    return mean
+
+
+def merge_delayed(theta0, snap, theta):
+    """theta_r <- theta0 - (snap_r - theta_r) in place for every worker; theta, snap [k][n]."""
+    k, n = theta.shape
+    dt = theta.dtype
+    fn = lib().oracle_merge_delayed_f32 if dt == np.float32 else lib().oracle_merge_delayed_f64
+    fn(_p(theta0, dt), _p(snap, dt), _p(theta, dt), k, n)
+
+
 # ---- layout -------------------------------------------------------------------
 def plan_layout(numel, align, tile):
     numel = np.ascontiguousarray(numel, dtype=np.uint64)
@@ -288,6 +313,22 @@ class DiLoCoOracle:
                 adamw_step_groups(st, g, self.groups, lr0 if lr is None else lr, b1, b2, eps)
             else:
                 adamw_step(st, g, lr0 if lr is None else lr, b1, b2, eps, wd)
+
+    def outer_begin(self):
+        """Round boundary of the delayed outer step: snapshot every worker's weights and compute
+        the outer update from the snapshots (theta0 and b change, the workers do not)."""
+        self.snap = np.stack([st.theta for st in self.workers])
+        return outer_update_from_snapshot(self.theta0, self.b, self.snap, self.outer_lr, self.mu,
+                                          self.pg_f16, self.round_mean)
+
+    def outer_finish(self):
+        """Delayed application: every worker moves to the new outer weights, keeping what it did
+        since the snapshot."""
+        theta = np.stack([st.theta for st in self.workers])
+        merge_delayed(self.theta0, self.snap, theta)
+        for r, st in enumerate(self.workers):
+            st.theta[:] = theta[r]
+        self.snap = None
 
     def outer_step(self):
         theta = np.stack([st.theta for st in self.workers])

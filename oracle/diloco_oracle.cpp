@@ -205,6 +205,20 @@ void nesterov_step(T* theta0, T* b, const T* grad, size_t n, double lr, double m
 
 }  // namespace
 
+// Step 2: delayed application.  theta0 holds the new outer weights; theta is [k][n], the
+// workers' current weights, updated in place.
+template <class T>
+static void merge_delayed(const T* theta0, const T* snap, T* theta, size_t k, size_t n) {
+  for (size_t r = 0; r < k; ++r) {
+    const T* s = snap + r * n;
+    T* th = theta + r * n;
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+      const T since_snapshot = s[i] - th[i];  // minus the worker's progress since the snapshot
+      th[i] = theta0[i] - since_snapshot;
+    }
+  }
+}
 extern "C" {
 
 // ---- binary16 casts --------------------------------------------------------
@@ -373,6 +387,42 @@ void oracle_outer_step_f32(float* theta0, float* b, float* theta, size_t k, size
   if (round_mean) round_through(mean_scratch, n, pg_dtype);
   nesterov_step<float>(theta0, b, mean_scratch, n, outer_lr, mu);
   for (size_t r = 0; r < k; ++r) std::memcpy(theta + r * n, theta0, n * sizeof(float));
+}
+
+// ---- delayed application of the outer step --------------------------------
+// The paper's future work (Conclusion; Section "Globally Distributed Training Setting", last
+// sentence) names averaging the weights asynchronously, interleaved with the computation of the
+// next round, without giving an update rule.  The rule taken here: at the round boundary each
+// worker's weights are snapshotted (sigma_r); the outer update is computed from the snapshots
+// exactly as the outer step computes it from the workers' weights (same pseudo-gradient,
+// rounding, average and Nesterov step), but the workers are not reset yet and keep stepping;
+// when the update is applied, each worker carries over what it has done since the snapshot:
+//     theta_r <- theta0_new - (sigma_r - theta_r).
+// With no steps in between, sigma_r - theta_r = +0 and the rule is the outer step of Figure 1.
+
+// Step 1: outer update from the snapshots.  snap is [k][n]; theta0 and b are updated in place;
+// the workers' weights are not read or written.
+void oracle_outer_update_from_snapshot_f32(float* theta0, float* b, const float* snap, size_t k,
+                                           size_t n, double outer_lr, double mu, int32_t pg_dtype,
+                                           int32_t round_mean, float* delta_scratch,
+                                           float* mean_scratch) {
+  for (size_t r = 0; r < k; ++r) {
+    pseudo_grad<float>(theta0, snap + r * n, delta_scratch + r * n, n);
+    round_through(delta_scratch + r * n, n, pg_dtype);
+  }
+  replica_mean<float>(delta_scratch, k, n, mean_scratch);
+  if (round_mean) round_through(mean_scratch, n, pg_dtype);
+  nesterov_step<float>(theta0, b, mean_scratch, n, outer_lr, mu);
+}
+
+// Step 2: delayed application (merge_delayed above).
+void oracle_merge_delayed_f32(const float* theta0, const float* snap, float* theta, size_t k,
+                              size_t n) {
+  merge_delayed<float>(theta0, snap, theta, k, n);
+}
+void oracle_merge_delayed_f64(const double* theta0, const double* snap, double* theta, size_t k,
+                              size_t n) {
+  merge_delayed<double>(theta0, snap, theta, k, n);
 }
 
 // ---- flat layout (written independently of the library's planner) ----------
