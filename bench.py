@@ -209,6 +209,56 @@ class Bench:
                 "outer_frac_min": min(r["outer_frac_median"] for r in runs),
                 "outer_frac_max": max(r["outer_frac_median"] for r in runs)}
 
+    def delayed_outer(self, name, k, pg, delay, reps):
+        """The delayed application of the outer step (update on a side stream from a snapshot,
+        merge later) next to the plain outer step: A = `delay` inner steps alone, B = begin +
+        finish with nothing in between, C = begin, `delay` inner steps, finish.  What the overlap
+        saves is A + B - C; both streams are HBM-bound, so it cannot be much."""
+        torch = self.torch
+        wl, dl, grads = self.make(name, k, pg=pg)
+        n = wl.n_params
+        snap = self.take(dl.grads_numel() * 4, torch.float32)
+        side = torch.cuda.Stream()
+
+        def seq_a():
+            for _ in range(delay):
+                dl.inner_step(grads)
+
+        def seq_b():
+            dl.outer_begin(snapshot=snap, side_stream=side)
+            dl.outer_finish()
+
+        def seq_c():
+            dl.outer_begin(snapshot=snap, side_stream=side)
+            for _ in range(delay):
+                dl.inner_step(grads)
+            dl.outer_finish()
+
+        for fn in (seq_a, seq_b, seq_c, dl.outer_step):
+            fn()
+        torch.cuda.synchronize()
+        med = lambda xs: sorted(xs)[len(xs) // 2]  # noqa: E731
+        t_sync = med(self.time_launches(dl.outer_step, reps))
+        t_a = med(self.time_launches(seq_a, reps))
+        t_b = med(self.time_launches(seq_b, reps))
+        t_c = med(self.time_launches(seq_c, reps))
+        dl.close()
+        del dl, grads, snap
+        bytes_delayed = (20 + 24 * k) * n   # snapshot 8k, update 16+4k, merge 4+12k bytes/element
+        return {"config": "%s x %d workers, %s pseudo-gradient, %d inner steps between begin and "
+                          "finish, medians of %d" % (name, k, {0: "f32", 1: "f16"}[pg], delay, reps),
+                "outer_step_ms": t_sync, "inner_steps_alone_ms": t_a,
+                "begin_finish_back_to_back_ms": t_b, "begin_inner_steps_finish_ms": t_c,
+                "saved_by_overlap_ms": t_a + t_b - t_c,
+                "extra_cost_over_plain_outer_step_ms": t_c - t_a - t_sync,
+                "bytes_begin_finish": bytes_delayed,
+                "begin_finish_GBps": bytes_delayed / t_b / 1e6,
+                "begin_finish_frac_of_peak": bytes_delayed / t_b / 1e6 / HBM_PEAK_GBS,
+                "note": "snapshot 8k + update (16+4k) + merge (4+12k) = (20+24k) B/element against "
+                        "(16+8k) for the plain outer step: on one GPU the delayed form costs more "
+                        "traffic and the overlap buys little, because both streams compete for "
+                        "the same HBM bandwidth"}
+
     def mixed_precision(self, k, reps):
         """Rows a1 + a2 in mixed precision: binary16 gradients scaled by 65536 on the 150M set
         plus 2000 ragged tensors; the inf/NaN check, then the inner step with the unscale fused."""
@@ -450,6 +500,7 @@ def main():
                              "runtime_k": B.quick("llama150m", kk, n_inner=0, n_outer=20,
                                                   tune=dict(outer_anyk=1))["outer"]}
                for kk in (4, 8)}}
+        out["delayed_outer"] = B.delayed_outer("llama150m", args.k, pg, 4, 10)
         out["tiny"] = dict(B.rounds("tiny", 2, 4, D.F32, 20, 2),
                            note="0.79M parameters x 2 workers: cache-resident and launch-bound, "
                                 "reported for completeness, not roofline-meaningful")

@@ -242,6 +242,33 @@ double diloco_lr_at(uint64_t step, uint64_t warmup_steps, uint64_t total_steps, 
  * propagate as IEEE arithmetic dictates.  Enqueues one kernel.  Errors: DILOCO_ERR_HIP. */
 int diloco_outer_step(diloco_ctx* ctx);
 
+/* Delayed application of the outer step: the asynchronous weight averaging, interleaved with the
+ * next round's computation, that the paper's Conclusion (and the last sentence of Section
+ * "Globally Distributed Training Setting") names as future work.  The paper gives no update
+ * rule; the one implemented:
+ *   diloco_outer_begin   at the round boundary copies every worker's weights into `snapshot`
+ *                        (sigma_r) on the context's stream, then computes on `side_stream`, from
+ *                        the snapshot, exactly what diloco_outer_step computes from the live
+ *                        weights -- pseudo-gradients theta0 - sigma_r, rounding, average, Nesterov
+ *                        step on theta0 and mom -- but resets no worker;
+ *   diloco_inner_step    may be called any number of times in between: the update touches
+ *                        theta0, mom and the snapshot only, so it can run at the same time;
+ *   diloco_outer_finish  makes the context's stream wait for the update and applies it:
+ *                        theta_r <- theta0_new - (sigma_r - theta_r) for every worker, which
+ *                        carries each worker's progress since the snapshot over to the new
+ *                        outer weights.
+ * With no inner step in between, the pair equals diloco_outer_step bit for bit (finite weights).
+ * snapshot: device, caller-owned, [k][stride] floats laid out like the worker weights
+ * (snapshot_bytes >= ((k-1)*stride + n_pad)*4), 16-byte aligned, untouched by the caller until
+ * diloco_outer_finish has run.  side_stream: hipStream_t of the same device (default priority);
+ * it may be the context's own stream, in which case nothing overlaps.  Between begin and finish
+ * theta0 and mom are in flux: diloco_outer_step and a second diloco_outer_begin return
+ * DILOCO_ERR_STATE, and so does diloco_outer_finish without a begin.  begin enqueues two
+ * kernels and two event operations, finish one kernel and one; none allocates.
+ * Errors: DILOCO_ERR_INVALID_ARG, DILOCO_ERR_ALIGN, DILOCO_ERR_STATE, DILOCO_ERR_HIP. */
+int diloco_outer_begin(diloco_ctx* ctx, void* snapshot, uint64_t snapshot_bytes, void* side_stream);
+int diloco_outer_finish(diloco_ctx* ctx);
+
 /* Device address of a flat buffer (replica ignored for THETA0 / MOM): the two model copies and
  * the optimizer states of paragraph "General Implementation Details", e.g. to view a worker's
  * parameter tensors in place at tensor_offsets.  Errors: DILOCO_ERR_INVALID_ARG. */

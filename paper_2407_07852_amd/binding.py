@@ -21,7 +21,7 @@ EXPORTS = ["diloco_query_layout", "diloco_init", "diloco_unscale_check", "diloco
            "diloco_outer_step", "diloco_get_buffer", "diloco_get_layout", "diloco_get_steps",
            "diloco_cast_f32_to_f16", "diloco_set_tuning", "diloco_last_error", "diloco_destroy",
            "diloco_set_param_groups", "diloco_lr_at", "diloco_cast_f32_to_bf16",
-           "diloco_inner_step_noalloc"]
+           "diloco_inner_step_noalloc", "diloco_outer_begin", "diloco_outer_finish"]
 
 
 class Config(C.Structure):
@@ -74,6 +74,8 @@ def lib():
         L.diloco_unscale_check.argtypes = [vp, vp, u64, i32, C.c_float, vp]
         L.diloco_inner_step.argtypes = [vp, vp, u64, i32, C.c_double, vp]
         L.diloco_outer_step.argtypes = [vp]
+        L.diloco_outer_begin.argtypes = [vp, vp, u64, vp]
+        L.diloco_outer_finish.argtypes = [vp]
         L.diloco_get_buffer.argtypes = [vp, C.c_int, u32, C.POINTER(vp)]
         L.diloco_get_layout.argtypes = [vp, C.POINTER(Layout)]
         L.diloco_get_steps.argtypes = [vp, C.POINTER(u32)]
@@ -142,6 +144,14 @@ def diloco_inner_step(ctx, grads_ptr, grad_stride, grad_dtype, lr=-1.0, found_in
 
 def diloco_outer_step(ctx):
     return _check(lib().diloco_outer_step(ctx), ctx)
+
+
+def diloco_outer_begin(ctx, snapshot_ptr, snapshot_bytes, side_stream=None):
+    return _check(lib().diloco_outer_begin(ctx, snapshot_ptr, snapshot_bytes, side_stream), ctx)
+
+
+def diloco_outer_finish(ctx):
+    return _check(lib().diloco_outer_finish(ctx), ctx)
 
 
 def diloco_get_buffer(ctx, which, replica=0):
@@ -283,6 +293,26 @@ class DiLoCo:
 
     def outer_step(self):
         return diloco_outer_step(self.ctx)
+
+    def outer_begin(self, snapshot=None, side_stream=None):
+        """Delayed outer step, first half.  snapshot: optional 1-D float32 device tensor of at
+        least grads_numel() elements (allocated and kept on first use otherwise); side_stream:
+        a torch stream for the update (a new default-priority stream otherwise)."""
+        if snapshot is None:
+            if getattr(self, "_snapshot", None) is None:
+                self._snapshot = torch.empty(self.grads_numel(), dtype=torch.float32,
+                                             device=self.device)
+            snapshot = self._snapshot
+        if side_stream is None:
+            if getattr(self, "_side", None) is None:
+                self._side = torch.cuda.Stream(device=self.device)
+            side_stream = self._side
+        self._snap_in_use, self._side_in_use = snapshot, side_stream
+        return diloco_outer_begin(self.ctx, snapshot.data_ptr(), snapshot.numel() * 4,
+                                  side_stream.cuda_stream)
+
+    def outer_finish(self):
+        return diloco_outer_finish(self.ctx)
 
     def steps(self):
         return diloco_get_steps(self.ctx, self.k)

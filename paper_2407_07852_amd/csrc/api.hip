@@ -36,6 +36,12 @@ struct diloco_ctx {
   uint32_t* d_chunk_group;         // device, [n_pad / 64] group id bytes, read as 32-bit words
   double lr_scale[DILOCO_MAX_GROUPS];
   double group_wd[DILOCO_MAX_GROUPS];
+  // delayed application of the outer step
+  hipEvent_t ev_snapshot;          // main stream: the snapshot is complete
+  hipEvent_t ev_update;            // side stream: theta0 and mom hold the new outer state
+  bool have_events;
+  bool outer_pending;              // between diloco_outer_begin and diloco_outer_finish
+  float* pending_snapshot;
   Tuning tune;
   std::string err;
 };
@@ -272,8 +278,15 @@ int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco
   c->checked_grads = nullptr;
   c->n_groups = 0;
   c->d_chunk_group = nullptr;
+  c->have_events = false;
+  c->outer_pending = false;
+  c->pending_snapshot = nullptr;
 
   auto bail = [&](int code) {
+    if (c->have_events) {
+      (void)hipEventDestroy(c->ev_snapshot);
+      (void)hipEventDestroy(c->ev_update);
+    }
     if (c->d_state) (void)hipFree(c->d_state);
     if (c->d_chunk_group) (void)hipFree(c->d_chunk_group);
     delete c;  // the message stays in the thread's buffer
@@ -304,6 +317,15 @@ int diloco_init(const diloco_config* cfg, const void* const* init_params, diloco
     e = scratch_on_current_device(&table, &dev);
     if (e != hipSuccess) return bail(fail_hip(c, "address of the static step table", e));
   }
+
+  e = hipEventCreateWithFlags(&c->ev_snapshot, hipEventDisableTiming);
+  if (e != hipSuccess) return bail(fail_hip(c, "hipEventCreate", e));
+  e = hipEventCreateWithFlags(&c->ev_update, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    (void)hipEventDestroy(c->ev_snapshot);
+    return bail(fail_hip(c, "hipEventCreate", e));
+  }
+  c->have_events = true;
 
   const uint32_t k = cfg->k_workers;
   // One allocation: the step state [k], then the per-step table [k].
@@ -533,12 +555,11 @@ double diloco_lr_at(uint64_t step, uint64_t warmup_steps, uint64_t total_steps, 
   return base_lr * (final_ratio + (1.0 - final_ratio) * cosine);
 }
 
-int diloco_outer_step(diloco_ctx* ctx) {
-  if (!ctx) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "ctx is NULL");
+static OuterArgs outer_args(const diloco_ctx* ctx, float* workers) {
   OuterArgs a;
   a.theta0 = buf(ctx, ctx->lay.off_theta0);
   a.mom = buf(ctx, ctx->lay.off_mom);
-  a.theta = buf(ctx, ctx->lay.off_theta);
+  a.theta = workers;
   a.stride = ctx->lay.stride;
   a.n_pad = ctx->lay.n_pad;
   a.lr = (float)ctx->cfg.outer_lr;
@@ -548,9 +569,69 @@ int diloco_outer_step(diloco_ctx* ctx) {
   a.k = (int)ctx->cfg.k_workers;
   a.pg = ctx->cfg.pg_dtype;
   a.round_mean = ctx->cfg.pg_round_mean;
+  return a;
+}
+
+int diloco_outer_step(diloco_ctx* ctx) {
+  if (!ctx) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "ctx is NULL");
+  if (ctx->outer_pending)
+    return fail(ctx, DILOCO_ERR_STATE, "a delayed outer step is pending: call diloco_outer_finish");
+  const OuterArgs a = outer_args(ctx, buf(ctx, ctx->lay.off_theta));
   hipError_t e = launch_outer(a, ctx->tune, ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, "outer step launch", e);
   ctx->steps_since_outer = 0;
+  return DILOCO_OK;
+}
+
+int diloco_outer_begin(diloco_ctx* ctx, void* snapshot, uint64_t snapshot_bytes, void* side_stream) {
+  if (!ctx) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "ctx is NULL");
+  if (ctx->outer_pending)
+    return fail(ctx, DILOCO_ERR_STATE, "a delayed outer step is already pending");
+  if (!snapshot) return fail(ctx, DILOCO_ERR_INVALID_ARG, "snapshot is NULL");
+  if (((uintptr_t)snapshot & 15u) != 0)
+    return fail(ctx, DILOCO_ERR_ALIGN, "snapshot must be 16-byte aligned");
+  const uint64_t k = ctx->cfg.k_workers;
+  const uint64_t need = ((k - 1) * ctx->lay.stride + ctx->lay.n_pad) * 4;
+  if (snapshot_bytes < need)
+    return fail(ctx, DILOCO_ERR_INVALID_ARG, "snapshot has %llu bytes, %llu are needed",
+                (unsigned long long)snapshot_bytes, (unsigned long long)need);
+  int rc = check_device_range(ctx, ctx->device, snapshot, need, "snapshot");
+  if (rc != DILOCO_OK) return rc;
+  const hipStream_t side = (hipStream_t)side_stream;
+  float* snap = static_cast<float*>(snapshot);
+  // main stream: snapshot of every worker's weights; everything enqueued earlier precedes it
+  hipError_t e = launch_snapshot(buf(ctx, ctx->lay.off_theta), snap, ctx->lay.stride,
+                                 ctx->lay.n_pad, (int)k, ctx->tune, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, "snapshot launch", e);
+  e = hipEventRecord(ctx->ev_snapshot, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, "hipEventRecord", e);
+  // side stream: the outer update from the snapshot.  It touches theta0, mom and the snapshot
+  // only, none of which an inner step reads or writes, so inner steps enqueued on the main
+  // stream from here on may run at the same time.
+  e = hipStreamWaitEvent(side, ctx->ev_snapshot, 0);
+  if (e != hipSuccess) return fail_hip(ctx, "hipStreamWaitEvent", e);
+  e = launch_outer_update(outer_args(ctx, snap), ctx->tune, side);
+  if (e != hipSuccess) return fail_hip(ctx, "outer update launch", e);
+  e = hipEventRecord(ctx->ev_update, side);
+  if (e != hipSuccess) return fail_hip(ctx, "hipEventRecord", e);
+  ctx->outer_pending = true;
+  ctx->pending_snapshot = snap;
+  ctx->steps_since_outer = 0;
+  return DILOCO_OK;
+}
+
+int diloco_outer_finish(diloco_ctx* ctx) {
+  if (!ctx) return fail(nullptr, DILOCO_ERR_INVALID_ARG, "ctx is NULL");
+  if (!ctx->outer_pending)
+    return fail(ctx, DILOCO_ERR_STATE, "no delayed outer step is pending");
+  hipError_t e = hipStreamWaitEvent(ctx->stream, ctx->ev_update, 0);
+  if (e != hipSuccess) return fail_hip(ctx, "hipStreamWaitEvent", e);
+  e = launch_merge_delayed(buf(ctx, ctx->lay.off_theta0), ctx->pending_snapshot,
+                           buf(ctx, ctx->lay.off_theta), ctx->lay.stride, ctx->lay.n_pad,
+                           (int)ctx->cfg.k_workers, ctx->tune, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, "merge launch", e);
+  ctx->outer_pending = false;
+  ctx->pending_snapshot = nullptr;
   return DILOCO_OK;
 }
 
@@ -637,6 +718,11 @@ const char* diloco_last_error(diloco_ctx* ctx) {
 int diloco_destroy(diloco_ctx* ctx) {
   if (!ctx) return DILOCO_OK;
   hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (ctx->outer_pending) (void)hipEventSynchronize(ctx->ev_update);  // side-stream work still reads the arena
+  if (ctx->have_events) {
+    (void)hipEventDestroy(ctx->ev_snapshot);
+    (void)hipEventDestroy(ctx->ev_update);
+  }
   hipError_t e2 = hipFree(ctx->d_state);
   if (ctx->d_chunk_group) {
     hipError_t e3 = hipFree(ctx->d_chunk_group);

@@ -58,7 +58,7 @@ struct InnerArgs {
 struct OuterArgs {
   float* theta0;
   float* mom;
-  float* theta;      // replica 0
+  float* theta;      // replica 0 (the delayed update reads the snapshot here instead)
   uint64_t stride;
   uint64_t n_pad;
   float lr, mu, kf, inv_kf;  // inv_kf = 1/k, used when k is a power of two (exact)
@@ -74,6 +74,15 @@ hipError_t launch_prologue(RepState* state, StepEntry* table, const int32_t* fou
 hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const Tuning& t,
                         hipStream_t s);
 hipError_t launch_outer(const OuterArgs& a, const Tuning& t, hipStream_t s);
+// Delayed application of the outer step: copy of every worker's weights into the snapshot; the
+// outer update computed from the snapshot (a.theta = snapshot; theta0 and mom updated, no
+// broadcast); and theta_r <- theta0 - (snapshot_r - theta_r).
+hipError_t launch_snapshot(const float* theta, float* snap, uint64_t stride, uint64_t n_pad, int k,
+                           const Tuning& t, hipStream_t s);
+hipError_t launch_outer_update(const OuterArgs& a, const Tuning& t, hipStream_t s);
+hipError_t launch_merge_delayed(const float* theta0, const float* snap, float* theta,
+                                uint64_t stride, uint64_t n_pad, int k, const Tuning& t,
+                                hipStream_t s);
 hipError_t launch_check(const void* g, uint64_t g_stride, uint64_t n_pad, int k, bool g16,
                         int32_t* found_inf, const Tuning& t, int n_cu, hipStream_t s);
 hipError_t launch_init_state(float* theta0, float* mom, float* theta, float* m, float* v,

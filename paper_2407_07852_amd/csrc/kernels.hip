@@ -241,7 +241,9 @@ __global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint3
 
 // Any k (run-time loop over the workers), in batches of up to 16 workers whose loads are all in
 // flight together; the sum still runs over the workers in ascending order.
-template <int PG, bool RM, int B>
+// BCAST = false is the delayed variant: a.theta is a snapshot of the workers' weights, theta0 and
+// mom are updated, and no worker is reset.
+template <int PG, bool RM, int B, bool BCAST>
 __global__ __launch_bounds__(B) void outer_fused_anyk_kernel(const OuterArgs a, uint32_t tiles) {
   constexpr bool NT = true;
   constexpr int kBatch = 16;
@@ -282,7 +284,42 @@ __global__ __launch_bounds__(B) void outer_fused_anyk_kernel(const OuterArgs a, 
   }
   st<NT>(t0_p + i, t0);
   st<NT>(b_p + i, b);
-  for (int r = 0; r < a.k; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0);
+  if constexpr (BCAST)
+    for (int r = 0; r < a.k; ++r) st<NT>(th_p + (size_t)r * rstride + i, t0);
+  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
+}
+
+// ------------------------------------------------------------------------------------------
+// Delayed application of the outer step (the asynchronous weight averaging the paper's
+// Conclusion names as future work): snapshot at the round boundary, and the later merge
+//   theta_r <- theta0_new - (snapshot_r - theta_r),
+// which keeps what each worker did since the snapshot.  Grid = (tiles, k) for both.
+// ------------------------------------------------------------------------------------------
+template <int B>
+__global__ __launch_bounds__(B) void snapshot_kernel(const float* __restrict__ theta,
+                                                     float* __restrict__ snap, uint64_t stride,
+                                                     uint32_t tiles) {
+  const size_t i = (size_t)blockIdx.y * (stride / kVecElems) + (size_t)blockIdx.x * B + threadIdx.x;
+  st<true>(reinterpret_cast<f32x4*>(snap) + i, ld<true>(reinterpret_cast<const f32x4*>(theta) + i));
+  if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
+}
+
+template <int B>
+__global__ __launch_bounds__(B) void merge_delayed_kernel(const float* __restrict__ theta0,
+                                                          const float* __restrict__ snap,
+                                                          float* __restrict__ theta, uint64_t stride,
+                                                          uint32_t tiles) {
+  const size_t e = (size_t)blockIdx.x * B + threadIdx.x;
+  const size_t i = (size_t)blockIdx.y * (stride / kVecElems) + e;
+  const f32x4 t0 = ld<true>(reinterpret_cast<const f32x4*>(theta0) + e);
+  const f32x4 sg = ld<true>(reinterpret_cast<const f32x4*>(snap) + i);
+  f32x4 th = ld<true>(reinterpret_cast<f32x4*>(theta) + i);
+#pragma unroll
+  for (int c = 0; c < kVecElems; ++c) {
+    const float since_snapshot = sg[c] - th[c];
+    th[c] = t0[c] - since_snapshot;
+  }
+  st<true>(reinterpret_cast<f32x4*>(theta) + i, th);
   if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
@@ -502,8 +539,8 @@ static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, hipStream_
   }
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
   const uint32_t lds = pad_lds_bytes(outer_shape(t, a.k, PG).waves, B, t.lds_per_cu);
-  hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM, B>), dim3((uint32_t)tiles), dim3(B), lds, s,
-                     a, (uint32_t)tiles);
+  hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM, B, true>), dim3((uint32_t)tiles), dim3(B), lds,
+                     s, a, (uint32_t)tiles);
   return hipGetLastError();
 }
 
@@ -523,6 +560,47 @@ hipError_t launch_outer(const OuterArgs& a, const Tuning& t, hipStream_t s) {
     case 2: return rm ? launch_outer_b<2, true>(a, t, s) : launch_outer_b<2, false>(a, t, s);
     default: return launch_outer_b<0, false>(a, t, s);  // FP32: rounding the mean is a no-op
   }
+}
+
+// The delayed update: k+2 read streams, 2 write streams; read-heavy traffic sustains more loads
+// in flight than the fused step (two more waves than its rule).
+template <int PG, bool RM>
+static hipError_t launch_outer_update_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
+  constexpr int B = 64;
+  const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
+  const int waves = auto_waves_outer(a.k > 16 ? 16 : a.k) + 2;
+  hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM, B, false>), dim3((uint32_t)tiles), dim3(B),
+                     pad_lds_bytes(waves, B, t.lds_per_cu), s, a, (uint32_t)tiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_outer_update(const OuterArgs& a, const Tuning& t, hipStream_t s) {
+  const bool rm = a.round_mean != 0;
+  switch (a.pg) {
+    case 1: return rm ? launch_outer_update_t<1, true>(a, t, s) : launch_outer_update_t<1, false>(a, t, s);
+    case 2: return rm ? launch_outer_update_t<2, true>(a, t, s) : launch_outer_update_t<2, false>(a, t, s);
+    default: return launch_outer_update_t<0, false>(a, t, s);
+  }
+}
+
+hipError_t launch_snapshot(const float* theta, float* snap, uint64_t stride, uint64_t n_pad, int k,
+                           const Tuning& t, hipStream_t s) {
+  constexpr int B = 64;
+  const uint64_t tiles = n_pad / (uint64_t)(B * kVecElems);
+  hipLaunchKernelGGL(snapshot_kernel<B>, dim3((uint32_t)tiles, (uint32_t)k), dim3(B),
+                     pad_lds_bytes(16, B, t.lds_per_cu), s, theta, snap, stride, (uint32_t)tiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_delayed(const float* theta0, const float* snap, float* theta,
+                                uint64_t stride, uint64_t n_pad, int k, const Tuning& t,
+                                hipStream_t s) {
+  constexpr int B = 64;
+  const uint64_t tiles = n_pad / (uint64_t)(B * kVecElems);
+  hipLaunchKernelGGL(merge_delayed_kernel<B>, dim3((uint32_t)tiles, (uint32_t)k), dim3(B),
+                     pad_lds_bytes(14, B, t.lds_per_cu), s, theta0, snap, theta, stride,
+                     (uint32_t)tiles);
+  return hipGetLastError();
 }
 
 template <int B, int V>

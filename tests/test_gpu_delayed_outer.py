@@ -1,0 +1,107 @@
+"""Delayed application of the outer step (diloco_outer_begin / diloco_outer_finish) against the
+oracle, bit for bit: the update runs on a side stream from a snapshot of the workers' weights
+while inner steps continue on the context's stream; the later merge keeps each worker's progress
+since the snapshot.  (The paper's Conclusion names this as future work; the rule is this
+build's reading.)"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from harness import (CpuSide, GpuSide, SampledCpuSide, compare, compare_state, gather_gpu,
+                     oracle_layout, sample_indices)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("pg,round_mean", [(False, False), (True, False), (oracle.PG_BF16, True)])
+@pytest.mark.parametrize("k,delay", [(2, 0), (3, 1), (8, 3), (11, 2)])
+def test_delayed_round_matches_oracle(k, delay, pg, round_mean):
+    wl = synth.Workload("ragged", [(300, 257), (4097,), (1,), (64, 64), (70001,)])
+    gpu, cpu = GpuSide(wl, k, pg, round_mean=round_mean), CpuSide(wl, k, pg, round_mean=round_mean)
+    step = 0
+    for rnd in range(2):
+        for _ in range(2):
+            gpu.dl.inner_step(gpu.gen_grads(step))
+            cpu.o.inner_step(cpu.gen_grads(step))
+            step += 1
+        gpu.dl.outer_begin()
+        cpu.o.outer_begin()
+        for _ in range(delay):                       # these overlap the side-stream update
+            gpu.dl.inner_step(gpu.gen_grads(step))
+            cpu.o.inner_step(cpu.gen_grads(step))
+            step += 1
+        gpu.dl.outer_finish()
+        cpu.o.outer_finish()
+        assert compare("theta0", gpu.host(gpu.dl.theta0), cpu.o.theta0, 0, 0) == 0
+        assert compare("mom", gpu.host(gpu.dl.mom), cpu.o.b, 0, 0) == 0
+        assert compare_state(gpu, cpu, 0, 0) == 0
+        if delay:
+            assert not np.array_equal(gpu.host(gpu.dl.theta[0]), gpu.host(gpu.dl.theta0))
+    assert gpu.dl.steps() == [step] * k
+    gpu.dl.close()
+
+
+def test_no_delay_equals_the_plain_outer_step():
+    wl = synth.tiny()
+    a, b = GpuSide(wl, 4, True), GpuSide(wl, 4, True)
+    for step in range(3):
+        a.dl.inner_step(a.gen_grads(step))
+        b.dl.inner_step(b.gen_grads(step))
+    a.dl.outer_step()
+    b.dl.outer_begin()
+    b.dl.outer_finish()
+    import torch
+    for x, y in ((a.dl.theta0, b.dl.theta0), (a.dl.mom, b.dl.mom), (a.dl.theta, b.dl.theta)):
+        assert torch.equal(x.view(torch.int32), y.view(torch.int32))
+    a.dl.close()
+    b.dl.close()
+
+
+def test_call_sequence_errors():
+    import paper_2407_07852_amd as D
+    import torch
+    dl = D.DiLoCo([1000], 2, fill_theta0=lambda t, lay, off: t.zero_())
+
+    def code(fn):
+        with pytest.raises(D.DilocoError) as e:
+            fn()
+        return e.value.code
+
+    assert code(dl.outer_finish) == D.ERR_STATE
+    small = torch.zeros(16, device="cuda")
+    assert code(lambda: dl.outer_begin(snapshot=small)) == D.ERR_INVALID_ARG
+    dl.outer_begin()
+    assert code(dl.outer_begin) == D.ERR_STATE
+    assert code(dl.outer_step) == D.ERR_STATE
+    dl.outer_finish()
+    dl.outer_step()
+    dl.close()
+
+
+@pytest.mark.timeout(900)
+def test_150m_k8_delayed_sampled():
+    """150M set, k = 8, FP16 pseudo-gradients: 3 inner steps, begin, 2 more inner steps while the
+    update runs, finish; sampled indices against the oracle."""
+    import torch
+    wl = synth.llama_150m()
+    k = 8
+    gpu = GpuSide(wl, k, True)
+    offsets, n_pad = oracle_layout(wl)
+    idx = sample_indices(wl, offsets, n_pad, every=4099 * 2)
+    cpu = SampledCpuSide(wl, k, idx, True)
+    idx_dev = torch.from_numpy(idx.astype(np.int64)).cuda()
+    for step in range(5):
+        if step == 3:
+            gpu.dl.outer_begin()
+            cpu.o.outer_begin()
+        gpu.dl.inner_step(gpu.gen_grads(step))
+        cpu.o.inner_step(cpu.gen_grads(step))
+    gpu.dl.outer_finish()
+    cpu.o.outer_finish()
+    assert compare("theta0", gather_gpu(gpu, gpu.dl.theta0, idx_dev), cpu.o.theta0, 0, 0) == 0
+    assert compare("mom", gather_gpu(gpu, gpu.dl.mom, idx_dev), cpu.o.b, 0, 0) == 0
+    got = gather_gpu(gpu, gpu.dl.theta, idx_dev)
+    for r in range(k):
+        assert compare("theta[%d]" % r, got[r], cpu.o.workers[r].theta, 0, 0) == 0
+    gpu.dl.close()
