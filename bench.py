@@ -69,7 +69,7 @@ class Bench:
         self.cursor = self.base
 
     # ------------------------------------------------------------------ set-up
-    def make(self, name, k, H=0, pg=0, round_mean=0, groups=False, g16=False):
+    def make(self, name, k, H=0, pg=0, round_mean=0, groups=False, g16=False, zeros=False):
         """A context on the named workload with seeded synthetic weights (matrices ~N(0, 0.02),
         norm vectors 1.0) and one resident seeded gradient set ~N(0, 1e-3) per worker."""
         torch, D, synth = self.torch, self.D, self.synth
@@ -108,6 +108,10 @@ class Bench:
                 synth.device_fill_f32(grads[r].data_ptr(), dl.layout.n_pad,
                                       synth.key(synth.STREAM_GRADS, r, 0), 1e-3,
                                       holder["kind"].data_ptr(), stream=self.stream.cuda_stream)
+        if zeros:   # all-zero weights and gradients: only for the data-dependence leg
+            dl.theta0.zero_()
+            dl.theta.zero_()
+            grads.zero_()
         torch.cuda.synchronize()
         return wl, dl, grads
 
@@ -165,10 +169,11 @@ class Bench:
             res["inner"] = stats(inner_ms, ib)
         return res
 
-    def quick(self, name, k, pg=0, round_mean=0, n_inner=20, n_outer=20, groups=False, tune=None):
+    def quick(self, name, k, pg=0, round_mean=0, n_inner=20, n_outer=20, groups=False, tune=None,
+              zeros=False):
         """Short timing of both kernels: n_inner inner and n_outer outer launches after two
         warm-up launches of each."""
-        wl, dl, grads = self.make(name, k, pg=pg, round_mean=round_mean, groups=groups)
+        wl, dl, grads = self.make(name, k, pg=pg, round_mean=round_mean, groups=groups, zeros=zeros)
         if tune:
             dl.set_tuning(**tune)
         n = wl.n_params
@@ -258,6 +263,79 @@ class Bench:
                         "(16+8k) for the plain outer step: on one GPU the delayed form costs more "
                         "traffic and the overlap buys little, because both streams compete for "
                         "the same HBM bandwidth"}
+
+    def stream_patterns(self, mib=1024, reps=10):
+        """What the machine sustains for plain streaming traffic of the same mixes and in the same
+        launch shape as the optimizer kernels (no arithmetic): pure reads, pure writes, a copy,
+        4 read + 3 write streams (the inner step's mix), 10 + 10 (the outer step's at k = 8).
+        Separate 1 GiB buffers of seeded random data; best residency of a small sweep."""
+        torch, synth = self.torch, self.synth
+        self.reset()
+        nbytes = mib << 20
+        bufs = [self.take(nbytes, torch.float32) for _ in range(20)]
+        for j, b in enumerate(bufs):
+            synth.device_fill_f32(b.data_ptr(), b.numel(), synth.key(synth.STREAM_WEIGHTS, j), 0.02,
+                                  stream=self.stream.cuda_stream)
+        sink = self.take(1024, torch.float32)
+        ptrs = [b.data_ptr() for b in bufs]
+        out = {"buffer_MiB": mib, "launches_timed": reps,
+               "note": "GB/s = (read + write streams) x buffer bytes / median launch time"}
+        # (name, read streams, write streams, written in place?, residencies tried)
+        cases = (("10R", 10, 0, False, (3, 4, 5, 6, 8, 12, 24)),
+                 ("10W", 0, 10, False, (2, 3, 4, 6, 8, 16)),
+                 ("1R+1W", 1, 1, False, (8, 16, 24, 32)),
+                 ("4R+3W", 4, 3, False, (8, 11, 14, 16)),
+                 ("4R+3W_in_place", 4, 3, True, (8, 11, 14, 16)),
+                 ("10R+10W", 10, 10, False, (2, 3, 4, 5, 6)),
+                 ("10R+10W_in_place", 10, 10, True, (3, 4, 5, 6)))
+        for nm, nr, nw, in_place, waves in cases:
+            # in place: the write streams are the first nw read streams, as in the optimizer
+            # kernels (theta, m, v rewritten; theta0, mom and every worker's weights rewritten)
+            use = ptrs[:nr] + (ptrs[:nw] if in_place else ptrs[nr:nr + nw])
+            best = None
+            for w in waves:
+                go = lambda: synth.device_stream_pattern(use, nr, nw, nbytes, w, sink.data_ptr(),  # noqa: E731
+                                                         self.stream.cuda_stream)
+                go()
+                go()
+                ms = sorted(self.time_launches(go, reps))[reps // 2]
+                gbps = (nr + nw) * nbytes / ms / 1e6
+                if best is None or gbps > best["GBps"]:
+                    best = {"GBps": gbps, "frac_of_peak": gbps / HBM_PEAK_GBS, "waves_per_cu": w,
+                            "ms_median": ms}
+            out[nm] = best
+        return out
+
+    def free_effect(self, gib, seconds=9.0):
+        """What freeing device memory does to a kernel that runs afterwards: inner steps of the
+        150M x 8 set are timed in bursts of 25 before, and for `seconds` after, a separate
+        allocation of `gib` GiB is made and freed (the one thing in this benchmark that frees)."""
+        torch = self.torch
+        wl, dl, grads = self.make("llama150m", 8)
+        ib = inner_bytes(wl.n_params, 8)
+
+        def burst():
+            ms = self.time_launches(lambda: dl.inner_step(grads), 25)
+            return ib / (sum(ms) / len(ms)) / 1e6 / HBM_PEAK_GBS
+
+        before = [burst() for _ in range(5)]
+        t0 = time.perf_counter()
+        big = torch.empty(gib << 30, dtype=torch.uint8, device="cuda")
+        del big
+        torch.cuda.empty_cache()
+        t_free = time.perf_counter() - t0
+        after = []
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            after.append((round(time.perf_counter() - t0, 2), burst()))
+        dl.close()
+        del dl, grads
+        lo = min(f for _, f in after)
+        recovered = next((t for t, f in after if f >= min(before) - 0.002 and
+                          all(g >= min(before) - 0.002 for tt, g in after if tt >= t)), None)
+        return {"freed_GiB": gib, "alloc_and_free_seconds": t_free,
+                "inner_frac_before": before, "inner_frac_after": after,
+                "inner_frac_lowest_after": lo, "seconds_until_back_to_normal": recovered}
 
     def mixed_precision(self, k, reps):
         """Rows a1 + a2 in mixed precision: binary16 gradients scaled by 65536 on the 150M set
@@ -377,6 +455,10 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--tune", nargs="*", default=[], metavar="NAME=VALUE",
                     help="launch-shape knobs applied to every context (diloco_set_tuning)")
+    ap.add_argument("--free-effect", type=int, default=0, metavar="GIB",
+                    help="instead of the benchmark: allocate and free this many GiB, and time the "
+                         "inner step before and for 9 s afterwards (the driver clears freed "
+                         "memory in the background)")
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MIB",
                     help="first run a plain copy kernel of this many MiB three times (reference "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -396,9 +478,9 @@ def main():
     tune = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.tune}
     # one device allocation for the whole run, sized for the largest leg (arena + FP32 gradients
     # + the generator's kind map), the placement legs' largest offset and alignment slack
-    full = not args.no_also and args.workload == "llama150m"
+    full = not args.no_also and args.workload == "llama150m" and not args.free_effect
     big = synth.WORKLOADS["llama1.1b" if full else args.workload]()
-    kk = max(args.k, 8) if full else args.k
+    kk = max(args.k, 8) if (full or args.free_effect) else args.k
     big_lay, _ = D.diloco_query_layout(D.make_config(big.numel, kk))
     pool_bytes = (big_lay.arena_bytes + ((kk - 1) * big_lay.stride + big_lay.n_pad) * 4
                   + big_lay.n_pad + (1100 << 20))
@@ -413,6 +495,10 @@ def main():
         torch.cuda.synchronize()
         del a, b
         torch.cuda.empty_cache()
+
+    if args.free_effect:
+        print(json.dumps({"free_effect": B.free_effect(args.free_effect)}))
+        return
 
     pgn = args.pg or ("f16" if args.workload == "llama1.1b" else "f32")
     pg = D.F16 if pgn == "f16" else D.F32
@@ -500,6 +586,13 @@ def main():
                              "runtime_k": B.quick("llama150m", kk, n_inner=0, n_outer=20,
                                                   tune=dict(outer_anyk=1))["outer"]}
                for kk in (4, 8)}}
+        out["data_dependence"] = {
+            "workload": "llama150m x %d workers, FP32 pseudo-gradient, 20 + 20 launches: the same "
+                        "kernels on all-zero weights and gradients against the synthetic values; "
+                        "what the memory system sustains depends on the data" % args.k,
+            "zeros": B.quick("llama150m", args.k, zeros=True),
+            "synthetic": B.quick("llama150m", args.k)}
+        out["stream_patterns"] = B.stream_patterns()
         out["delayed_outer"] = B.delayed_outer("llama150m", args.k, pg, 4, 10)
         out["tiny"] = dict(B.rounds("tiny", 2, 4, D.F32, 20, 2),
                            note="0.79M parameters x 2 workers: cache-resident and launch-bound, "

@@ -94,6 +94,8 @@ def device():
         L.synth_device_fill_f16.restype = i
         L.synth_device_copy.argtypes = [vp, vp, sz, vp]
         L.synth_device_copy.restype = i
+        L.synth_device_stream_pattern.argtypes = [C.POINTER(vp), i, i, sz, i, vp, vp]
+        L.synth_device_stream_pattern.restype = i
         _device = L
     return _device
 
@@ -225,3 +227,12 @@ def device_copy(dst_ptr, src_ptr, n_bytes, stream=None):
     rc = device().synth_device_copy(dst_ptr, src_ptr, n_bytes, stream)
     if rc != 0:
         raise RuntimeError("synth_device_copy: hip error %d" % rc)
+
+
+def device_stream_pattern(buf_ptrs, nr, nw, n_bytes, waves_per_cu, sink_ptr, stream=None):
+    """One launch of the streaming reference pattern: nr read + nw write streams of n_bytes each
+    (device addresses in buf_ptrs), residency capped at waves_per_cu waves per CU."""
+    arr = (C.c_void_p * len(buf_ptrs))(*buf_ptrs)
+    rc = device().synth_device_stream_pattern(arr, nr, nw, n_bytes, waves_per_cu, sink_ptr, stream)
+    if rc != 0:
+        raise RuntimeError("synth_device_stream_pattern: error %d" % rc)
