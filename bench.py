@@ -281,7 +281,9 @@ class Bench:
         out = {"buffer_MiB": mib, "launches_timed": reps,
                "note": "GB/s = (read + write streams) x buffer bytes / median launch time"}
         # (name, read streams, write streams, written in place?, residencies tried)
-        cases = (("10R", 10, 0, False, (3, 4, 5, 6, 8, 12, 24)),
+        cases = (("1R", 1, 0, False, (8, 16, 24, 32)),
+                 ("4R", 4, 0, False, (6, 8, 12, 16, 24)),
+                 ("10R", 10, 0, False, (3, 4, 5, 6, 8, 12, 24)),
                  ("10W", 0, 10, False, (2, 3, 4, 6, 8, 16)),
                  ("1R+1W", 1, 1, False, (8, 16, 24, 32)),
                  ("4R+3W", 4, 3, False, (8, 11, 14, 16)),

@@ -128,7 +128,8 @@ int synth_device_copy(void* dst, const void* src, size_t n_bytes, void* stream) 
 
 // One launch of a streaming pattern: nr read streams (bufs[0..nr)) and nw write streams
 // (bufs[nr..nr+nw)), each n_bytes long (a multiple of 1024), at most waves_per_cu single-wave
-// workgroups resident per CU (0 = no cap).  Supported (nr, nw): (10,0) (0,10) (1,1) (4,3) (10,10).
+// workgroups resident per CU (0 = no cap).  Supported (nr, nw): (1,0) (4,0) (10,0) (0,10) (1,1)
+// (4,3) (10,10).
 // sink: device, at least 4 bytes.  Returns the hipError_t of the launch, or -1 for an unsupported
 // pattern.
 int synth_device_stream_pattern(void* const* bufs, int nr, int nw, size_t n_bytes, int waves_per_cu,
@@ -144,6 +145,8 @@ int synth_device_stream_pattern(void* const* bufs, int nr, int nw, size_t n_byte
   const size_t n_vec = n_bytes / 16;
   hipStream_t st = (hipStream_t)stream;
   float* sk = (float*)sink;
+  if (nr == 1 && nw == 0) return launch_pattern<1, 0>(s, sk, n_vec, lds, st);
+  if (nr == 4 && nw == 0) return launch_pattern<4, 0>(s, sk, n_vec, lds, st);
   if (nr == 10 && nw == 0) return launch_pattern<10, 0>(s, sk, n_vec, lds, st);
   if (nr == 0 && nw == 10) return launch_pattern<0, 10>(s, sk, n_vec, lds, st);
   if (nr == 1 && nw == 1) return launch_pattern<1, 1>(s, sk, n_vec, lds, st);
