@@ -119,16 +119,23 @@ class Bench:
         pass  # nothing is freed between legs: see the class comment
 
     # ------------------------------------------------------------------ timing
-    def time_launches(self, fn, n):
-        """n calls of fn, each bracketed by events on the launch stream; -> list of ms."""
+    def time_sequence(self, fns):
+        """Calls every function of the list in order, each bracketed by events on the launch
+        stream, with no host synchronisation in between (so the queue never runs dry and no
+        host launch latency lands inside a bracket); -> list of ms, one per call."""
         torch = self.torch
+        n = len(fns)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
         ev[0].record(self.stream)
-        for i in range(n):
+        for i, fn in enumerate(fns):
             fn()
             ev[i + 1].record(self.stream)
         ev[n].synchronize()
         return [ev[i].elapsed_time(ev[i + 1]) for i in range(n)]
+
+    def time_launches(self, fn, n):
+        """n calls of fn, each bracketed by events on the launch stream; -> list of ms."""
+        return self.time_sequence([fn] * n)
 
     def rounds(self, name, k, H, pg, rounds, warmup_rounds, warmup_inner=None, extra_outer=0,
                groups=False):
@@ -146,9 +153,11 @@ class Bench:
         torch.cuda.synchronize()
         inner_ms, outer_ms = [], []
         t0 = time.perf_counter()
+        step = lambda: dl.inner_step(grads)  # noqa: E731
         for _ in range(rounds):
-            inner_ms += self.time_launches(lambda: dl.inner_step(grads), H)
-            outer_ms += self.time_launches(dl.outer_step, 1)
+            ms = self.time_sequence([step] * H + [dl.outer_step])
+            inner_ms += ms[:H]
+            outer_ms += ms[H:]
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
         in_round_ms = list(outer_ms)
