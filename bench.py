@@ -297,10 +297,10 @@ class Bench:
                  ("10R", 10, 0, False, (3, 4, 5, 6, 8, 12, 24)),
                  ("10W", 0, 10, False, (2, 3, 4, 6, 8, 16)),
                  ("1R+1W", 1, 1, False, (8, 16, 24, 32)),
-                 ("4R+3W", 4, 3, False, (8, 11, 14, 16)),
-                 ("4R+3W_in_place", 4, 3, True, (8, 11, 14, 16)),
+                 ("4R+3W", 4, 3, False, (8, 9, 10, 11, 12, 14)),
+                 ("4R+3W_in_place", 4, 3, True, (8, 9, 10, 11, 12, 14)),
                  ("10R+10W", 10, 10, False, (2, 3, 4, 5, 6)),
-                 ("10R+10W_in_place", 10, 10, True, (3, 4, 5, 6)))
+                 ("10R+10W_in_place", 10, 10, True, (2, 3, 4, 5, 6)))
         for nm, nr, nw, in_place, waves in cases:
             # in place: the write streams are the first nw read streams, as in the optimizer
             # kernels (theta, m, v rewritten; theta0, mom and every worker's weights rewritten)

@@ -418,29 +418,26 @@ __global__ __launch_bounds__(kBlock) void cast_kernel(const float* __restrict__ 
   }
 }
 
-// Dynamic LDS bytes per workgroup so that at most `waves_per_cu` waves of B-thread workgroups
-// are resident on a CU with `lds_per_cu` bytes of LDS (0 = no cap).
-// Automatic residency from the bytes of loads one wave has in flight.  Measured optima on
-// MI355X: the inner step wants about 44 KiB of loads in flight per CU (11 waves x 4 KiB), the
-// outer step about 40 KiB for every k (k=1: 14 waves x 3 KiB, k=2: 10 x 4, k=4: 6 x 6,
-// k=8: 4 x 10); one wave more or less costs 1-3 %.
-int auto_waves(int load_bytes_per_wave, int target_bytes_per_cu, bool round_to_nearest) {
-  const int w = (target_bytes_per_cu + (round_to_nearest ? load_bytes_per_wave / 2 : 0)) /
-                load_bytes_per_wave;
-  return w < 2 ? 2 : (w > 16 ? 16 : w);
-}
-int auto_waves_inner(int load_bytes_per_wave) {
-  return auto_waves(load_bytes_per_wave, 44 * 1024, true);
-}
-int auto_waves_outer(int k) { return auto_waves((k + 2) * 1024, 40 * 1024, false); }
+// Residency.  The mixed read/write streaming kernels run fastest with a LIMITED number of waves
+// resident per CU (40-50 KiB of loads in flight per CU; more in-flight requests lower the
+// sustained HBM bandwidth, fewer starve it).  Measured optima on MI355X, the same at the 150M and
+// the 1.1B size: the inner step wants 10 waves of 4 KiB loads each (11 with one or two workers,
+// 12 with binary16 gradients, whose waves load 3.5 KiB); the outer step is tabulated per k below.
+int inner_waves_auto(int k, bool g16) { return g16 ? 12 : (k <= 2 ? 11 : 10); }
+
+// The hardware hands out LDS in granules of 1280 bytes (160 KiB / 128): a request is rounded up
+// to whole granules, and that, not the runtime's occupancy query, decides how many workgroups fit
+// (measured: 54272 bytes leave 2 workgroups per CU, 53248 leave 3; 32768 leave 4, 32000 leave 5).
+// The pad is therefore a whole number of granules.
+constexpr uint32_t kLdsGranule = 1280;
 
 uint32_t pad_lds_bytes(int waves_per_cu, int block, uint32_t lds_per_cu) {
   if (waves_per_cu <= 0) return 0;
   int groups = waves_per_cu / (block / 64);
   if (groups < 1) groups = 1;
   if (groups >= 32) return 0;
-  uint32_t bytes = (lds_per_cu / (uint32_t)groups) & ~511u;
-  if (bytes > 65536u) bytes = 65536u;  // default per-workgroup limit; caps at 2 groups per CU
+  uint32_t bytes = lds_per_cu / (uint32_t)groups / kLdsGranule * kLdsGranule;
+  if (bytes > 64000u) bytes = 64000u;  // 50 granules, under the 64 KiB per-workgroup limit: 2 groups
   return bytes;
 }
 
@@ -471,7 +468,7 @@ template <int B, bool G16, bool GROUPS>
 static hipError_t launch_inner_t(const InnerArgs& a, int k, const Tuning& t, hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
   const dim3 grid((uint32_t)tiles, (uint32_t)k);
-  const int waves = t.inner_waves < 0 ? auto_waves_inner(G16 ? 3584 : 4096) : t.inner_waves;
+  const int waves = t.inner_waves < 0 ? inner_waves_auto(k, G16) : t.inner_waves;
   const uint32_t lds = pad_lds_bytes(waves, B, t.lds_per_cu);
   hipLaunchKernelGGL((adamw_flat_kernel<B, G16, GROUPS>), grid, dim3(B), lds, s, a,
                      (uint32_t)tiles);
@@ -495,21 +492,22 @@ hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const 
 }
 
 // Launch shape of the outer step: threads per workgroup and resident waves per CU, by k and
-// pseudo-gradient type.  Measured optima on MI355X at the 150M and the 1.1B set (medians of 12-20
-// launches; the best shape is the same at both sizes): with few streams (k <= 2) two-wave
-// workgroups, which put 2 KiB of every stream in flight from one CU at the same moment, gain 1-2
-// points; from k = 3 on single-wave workgroups are as fast or faster and never fall off a cliff
-// (two-wave workgroups lose 5-15 points at some k / type combinations).  The reduced-precision
-// modes' conversions lengthen each wave's compute phase, which at k = 4, 5 wants one more wave.
+// pseudo-gradient type.  Measured optima on MI355X at the 150M and the 1.1B set (medians of 10-16
+// launches; the best shape is the same at both sizes): single-wave workgroups throughout (two-wave
+// workgroups, which put 2 KiB of every stream in flight from one CU at the same moment, tie at
+// k <= 2 and lose 1-15 points from k = 3 on), and 9, 6, 6, 4, 4, 4, 5, 4 waves for k = 1..8.  The
+// reduced-precision modes' conversions lengthen each wave's compute phase, which at k = 2, 4, 5
+// wants one more wave.  One wave off the optimum costs 0.5-5 points.  The run-time-k kernel
+// (k >= 9) holds up to 16 workers' loads per wave and wants 4.
 struct OuterShape { int block, waves; };
 static OuterShape outer_shape(const Tuning& t, int k, int pg) {
-  static const int kWaves32[9] = {0, 12, 10, 7, 5, 5, 5, 6, 5};
-  static const int kWaves16[9] = {0, 12, 10, 7, 6, 6, 5, 6, 5};
+  static const int kWaves32[9] = {0, 9, 6, 6, 4, 4, 4, 5, 4};
+  static const int kWaves16[9] = {0, 9, 7, 6, 5, 5, 4, 5, 4};
   OuterShape s;
-  s.block = t.outer_block > 0 ? t.outer_block : (k <= 2 ? 128 : 64);
+  s.block = t.outer_block > 0 ? t.outer_block : 64;
   if (t.outer_waves >= 0) s.waves = t.outer_waves;
   else if (k <= 8) s.waves = pg != 0 ? kWaves16[k] : kWaves32[k];
-  else s.waves = auto_waves_outer(k > 16 ? 16 : k);  // 16 workers' loads per batch
+  else s.waves = 4;
   return s;
 }
 
@@ -563,12 +561,12 @@ hipError_t launch_outer(const OuterArgs& a, const Tuning& t, hipStream_t s) {
 }
 
 // The delayed update: k+2 read streams, 2 write streams; read-heavy traffic sustains more loads
-// in flight than the fused step (two more waves than its rule).
+// in flight than the fused step (one more wave than the run-time-k kernel's 4).
 template <int PG, bool RM>
 static hipError_t launch_outer_update_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
   constexpr int B = 64;
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
-  const int waves = auto_waves_outer(a.k > 16 ? 16 : a.k) + 2;
+  const int waves = 5;
   hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM, B, false>), dim3((uint32_t)tiles), dim3(B),
                      pad_lds_bytes(waves, B, t.lds_per_cu), s, a, (uint32_t)tiles);
   return hipGetLastError();

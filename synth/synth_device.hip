@@ -139,8 +139,9 @@ int synth_device_stream_pattern(void* const* bufs, int nr, int nw, size_t n_byte
   for (int j = 0; j < nr + nw; ++j) s.p[j] = (f32x4*)bufs[j];
   unsigned lds = 0;
   if (waves_per_cu > 0 && waves_per_cu < 32) {
-    lds = (unsigned)((160u * 1024u / (unsigned)waves_per_cu) & ~511u);
-    if (lds > 65536u) lds = 65536u;
+    // whole 1280-byte granules, the unit in which the hardware hands out LDS
+    lds = 160u * 1024u / (unsigned)waves_per_cu / 1280u * 1280u;
+    if (lds > 64000u) lds = 64000u;
   }
   const size_t n_vec = n_bytes / 16;
   hipStream_t st = (hipStream_t)stream;
