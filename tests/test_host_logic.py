@@ -108,6 +108,37 @@ def test_no_gpu_means_a_loud_error_not_a_fallback():
     assert e.value.code == D.ERR_HIP
 
 
+def test_noalloc_entry_point_validates_on_the_host_before_touching_the_gpu():
+    """Argument errors of diloco_inner_step_noalloc are found on the host (the pointers are never
+    dereferenced); valid arguments without a GPU end in a HIP error, not in a fallback."""
+    import torch
+    D = _D()
+    base = dict(theta=4096, m=8192, v=12288, stride=8192, n_pad=8192, k_workers=2, grad_dtype=D.F32,
+                grads=16384, grad_stride=8192, inv_scale=1.0, found_inf=None, step_state=256,
+                lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, stream=None)
+
+    def code(**kw):
+        with pytest.raises(D.DilocoError) as e:
+            D.diloco_inner_step_noalloc(**dict(base, **kw))
+        return e.value.code, str(e.value)
+
+    c, msg = code(k_workers=65)
+    assert c == D.ERR_INVALID_ARG and "static step table" in msg
+    assert code(k_workers=0)[0] == D.ERR_INVALID_ARG
+    assert code(theta=None)[0] == D.ERR_INVALID_ARG
+    assert code(n_pad=8191)[0] == D.ERR_INVALID_ARG
+    assert code(stride=4096)[0] == D.ERR_INVALID_ARG
+    assert code(grad_dtype=D.BF16)[0] == D.ERR_INVALID_ARG
+    assert code(theta=4100)[0] == D.ERR_ALIGN
+    assert code(grad_stride=8196)[0] == D.ERR_ALIGN
+    assert code(beta1=1.0)[0] == D.ERR_INVALID_ARG
+    assert code(eps=0.0)[0] == D.ERR_INVALID_ARG
+    assert code(inv_scale=0.0)[0] == D.ERR_INVALID_ARG
+    assert code(grad_dtype=D.F16)[0] == D.ERR_STATE          # binary16 gradients need flags
+    if not torch.cuda.is_available():
+        assert code()[0] == D.ERR_HIP
+
+
 def _mix64(z):
     M = (1 << 64) - 1
     z ^= z >> 30

@@ -64,6 +64,41 @@ def test_noalloc_inner_step_matches_the_context_path_twice_in_a_row():
     one_case(torch, D, [9000, 100], 2, steps=2, flagged=1, seed=2)
 
 
+def test_noalloc_with_binary16_gradients_and_flags():
+    """binary16 gradients under a loss scale through the entry point that allocates nothing: the
+    flags come from a context's check of the same buffer; results equal the context path's."""
+    import torch
+    import paper_2407_07852_amd as D
+    k, numel = 3, [20000, 513]
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    ref = D.DiLoCo(numel, k, fill_theta0=lambda t, lay, off: t.normal_(0, 0.02, generator=gen), **HP)
+    L = ref.layout
+    span = (k - 1) * L.stride + L.n_pad
+    cand = [torch.zeros(span, dtype=torch.float32, device="cuda") for _ in range(3)]
+    views = [torch.as_strided(c, (k, L.n_pad), (L.stride, 1)) for c in cand]
+    views[0].copy_(ref.theta)
+    state = fresh_state(torch, k)
+    g = ref.new_grads(torch.float16)
+    flags = ref.new_flags()
+    inv = 1.0 / 1024
+    for step in range(2):
+        g.copy_((torch.randn(g.shape, generator=gen, device="cuda") * 1.0).to(torch.float16))
+        if step == 0:
+            g[2, 100] = float("nan")
+        ref.unscale_check(g, inv, flags)
+        assert flags.cpu().tolist() == [0, 0, int(step == 0)]
+        ref.inner_step(g, flags=flags)
+        D.diloco_inner_step_noalloc(
+            theta=cand[0].data_ptr(), m=cand[1].data_ptr(), v=cand[2].data_ptr(), stride=L.stride,
+            n_pad=L.n_pad, k_workers=k, grad_dtype=D.F16, grads=g.data_ptr(), grad_stride=g.stride(0),
+            inv_scale=inv, found_inf=flags.data_ptr(), step_state=state.data_ptr(),
+            lr=HP["inner_lr"], beta1=HP["beta1"], beta2=HP["beta2"], eps=HP["eps"],
+            weight_decay=HP["weight_decay"], stream=torch.cuda.current_stream().cuda_stream)
+        for name, got, want in zip("theta m v".split(), views, (ref.theta, ref.m, ref.v)):
+            assert torch.equal(got.view(torch.int32), want.view(torch.int32)), (name, step)
+    ref.close()
+
+
 def test_noalloc_rejects_what_it_cannot_hold():
     import torch
     import paper_2407_07852_amd as D
