@@ -468,6 +468,12 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--tune", nargs="*", default=[], metavar="NAME=VALUE",
                     help="launch-shape knobs applied to every context (diloco_set_tuning)")
+    ap.add_argument("--settle", type=float, default=10.0, metavar="SECONDS",
+                    help="wait this long before the run's one device allocation is made.  The "
+                         "driver clears device memory freed by earlier processes in the "
+                         "background (about 34 GB/s, so up to 9 s for a whole GPU); an allocation "
+                         "made meanwhile is placed elsewhere physically, and at the 1.1B size "
+                         "that moves the kernels by up to 2 points either way")
     ap.add_argument("--free-effect", type=int, default=0, metavar="GIB",
                     help="instead of the benchmark: allocate and free this many GiB, and time the "
                          "inner step before and for 9 s afterwards (the driver clears freed "
@@ -497,6 +503,9 @@ def main():
     big_lay, _ = D.diloco_query_layout(D.make_config(big.numel, kk))
     pool_bytes = (big_lay.arena_bytes + ((kk - 1) * big_lay.stride + big_lay.n_pad) * 4
                   + big_lay.n_pad + (1100 << 20))
+    if args.settle > 0:
+        torch.cuda.init()
+        time.sleep(args.settle)
     B = Bench(torch, D, synth, tune, pool_bytes)
 
     if args.calibration_copy:
@@ -547,7 +556,8 @@ def main():
                                "pseudo-gradient" % (main_res["workload"], args.k, args.h, pgn),
                    "n_params": main_res["n_params"], "k_workers": args.k, "H": args.h,
                    "pg_dtype": pgn, "step": "one round = H inner launches + 1 outer launch",
-                   "tuning_overrides": tune, "commit": git_head(root)},
+                   "tuning_overrides": tune, "commit": git_head(root),
+                   "settle_seconds_before_allocating": args.settle},
         "outer_step": main_res["outer"], "outer_step_ms": main_res["outer"]["ms"],
         "outer_step_in_rounds": main_res["outer_in_rounds"],
         "finite": main_res["finite"],
