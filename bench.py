@@ -350,6 +350,52 @@ class Bench:
                 "inner_frac_before": before, "inner_frac_after": after,
                 "inner_frac_lowest_after": lo, "seconds_until_back_to_normal": recovered}
 
+    def tiny_graph(self, k, H, rounds):
+        """Tiny is launch-bound (2 launches per inner step, 1 per outer step, a few microseconds
+        of work each), which is what HIP graphs are for: one whole round (H inner steps + the
+        outer step) captured once and replayed, against the same round launched eagerly.  The
+        step state lives on the device, so the captured round replays correctly any number of
+        times (tests/test_gpu_graph_capture.py checks replays against the oracle)."""
+        torch = self.torch
+        side = torch.cuda.Stream()
+        main_stream = self.stream
+        self.stream = side                       # the context borrows the capturing stream
+        try:
+            with torch.cuda.stream(side):
+                wl, dl, grads = self.make("tiny", k, H=H)
+
+                def one_round():
+                    for _ in range(H):
+                        dl.inner_step(grads)
+                    dl.outer_step()
+
+                one_round()
+                side.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(rounds):
+                    one_round()
+                side.synchronize()
+                eager_us = (time.perf_counter() - t0) / rounds * 1e6
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    one_round()
+                graph.replay()
+                side.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(rounds):
+                    graph.replay()
+                side.synchronize()
+                graph_us = (time.perf_counter() - t0) / rounds * 1e6
+                steps = dl.steps()
+                dl.close()
+                del graph, dl, grads
+        finally:
+            self.stream = main_stream
+        assert steps == [H * (2 * rounds + 2)] * k, steps
+        return {"config": "tiny x %d workers, one round = %d inner steps + 1 outer step (%d kernel "
+                          "launches), wall time per round over %d rounds" % (k, H, 2 * H + 1, rounds),
+                "eager_us_per_round": eager_us, "graph_replay_us_per_round": graph_us}
+
     def mixed_precision(self, k, reps):
         """Rows a1 + a2 in mixed precision: binary16 gradients scaled by 65536 on the 150M set
         plus 2000 ragged tensors; the inf/NaN check, then the inner step with the unscale fused."""
@@ -622,6 +668,7 @@ def main():
         out["tiny"] = dict(B.rounds("tiny", 2, 4, D.F32, 20, 2),
                            note="0.79M parameters x 2 workers: cache-resident and launch-bound, "
                                 "reported for completeness, not roofline-meaningful")
+        out["tiny_graph"] = B.tiny_graph(2, 4, 200)
     if not args.no_cpu:
         cb = cpu_baseline(args.k)
         n = main_res["n_params"]
