@@ -105,3 +105,40 @@ def test_150m_k8_delayed_sampled():
     for r in range(k):
         assert compare("theta[%d]" % r, got[r], cpu.o.workers[r].theta, 0, 0) == 0
     gpu.dl.close()
+
+
+@pytest.mark.timeout(900)
+def test_1_1b_k8_delayed_sampled_with_groups():
+    """The largest configuration (1.1B set, k = 8, FP16 pseudo-gradients), with parameter groups
+    on a warm-up schedule: 2 inner steps, begin, 1 inner step while the update runs on the side
+    stream, finish; sampled indices against the oracle."""
+    import torch
+    from harness import order_by_group
+    wl = synth.llama_1_1b()
+    k = 8
+    grp = [1 if v else 0 for v in wl.is_vector]
+    grp[-1] = grp[-2] = 2
+    scale, wd = [1.0, 1.0, 0.5], [0.1, 0.0, 0.0]
+    gpu = GpuSide(wl, k, True)
+    gpu.set_groups(grp, scale, wd)
+    offsets, n_pad = oracle_layout(wl)
+    idx = order_by_group(sample_indices(wl, offsets, n_pad, every=4099 * 16), offsets, grp)
+    cpu = SampledCpuSide(wl, k, idx, True)
+    cpu.set_groups(grp, scale, wd)
+    idx_dev = torch.from_numpy(idx.astype(np.int64)).cuda()
+    for step in range(3):
+        if step == 2:
+            gpu.dl.outer_begin()
+            cpu.o.outer_begin()
+        lr = oracle.lr_at(step + 1, 1000, 0, 4e-4)
+        gpu.dl.inner_step(gpu.gen_grads(step), lr=lr)
+        cpu.o.inner_step(cpu.gen_grads(step), lr=lr)
+    gpu.dl.outer_finish()
+    cpu.o.outer_finish()
+    assert compare("theta0", gather_gpu(gpu, gpu.dl.theta0, idx_dev), cpu.o.theta0, 0, 0) == 0
+    assert compare("mom", gather_gpu(gpu, gpu.dl.mom, idx_dev), cpu.o.b, 0, 0) == 0
+    for name, dev in (("theta", gpu.dl.theta), ("m", gpu.dl.m), ("v", gpu.dl.v)):
+        got = gather_gpu(gpu, dev, idx_dev)
+        for r in range(k):
+            assert compare("%s[%d]" % (name, r), got[r], getattr(cpu.o.workers[r], name), 0, 0) == 0
+    gpu.dl.close()
