@@ -156,6 +156,10 @@ int diloco_unscale_check(diloco_ctx* ctx, const void* grads, uint64_t grad_strid
  * marks the worker inactive) and the AdamW kernel that reads the prologue's table.  The step
  * state lives on the device only, so a captured sequence with any number of inner steps, odd
  * included, replays correctly and can be mixed with eager calls.
+ * The gradient buffer's extent is checked against its allocation when the pointer is first
+ * passed; calls that repeat the last validated pointer (the steady state of a training loop)
+ * skip the two runtime queries, so a buffer freed and re-allocated smaller at the same address
+ * between two calls is the caller's responsibility.
  * Errors: DILOCO_ERR_INVALID_ARG, DILOCO_ERR_ALIGN, DILOCO_ERR_STATE, DILOCO_ERR_HIP. */
 int diloco_inner_step(diloco_ctx* ctx, const void* grads, uint64_t grad_stride,
                       int32_t grad_dtype, double lr, const int32_t* found_inf);
