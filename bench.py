@@ -275,7 +275,7 @@ class Bench:
                         "traffic and the overlap buys little, because both streams compete for "
                         "the same HBM bandwidth"}
 
-    def stream_patterns(self, mib=1024, reps=10):
+    def stream_patterns(self, mib=1024, reps=20):
         """What the machine sustains for plain streaming traffic of the same mixes and in the same
         launch shape as the optimizer kernels (no arithmetic): pure reads, pure writes, a copy,
         4 read + 3 write streams (the inner step's mix), 10 + 10 (the outer step's at k = 8).
@@ -625,7 +625,7 @@ def main():
                        "finite": also["finite"]}
         out["placement_spread"] = {
             "llama150m": B.placement_spread("llama150m", args.k, pg, 20, 20),
-            "llama1.1b": B.placement_spread("llama1.1b", args.k, D.F16, 10, 20)}
+            "llama1.1b": B.placement_spread("llama1.1b", args.k, D.F16, 20, 20)}
         out["mixed_precision"] = B.mixed_precision(4, 20)
         out["param_groups"] = {
             "config": {"workload": "llama150m and llama1.1b x %d workers, 3 parameter groups (norm "
@@ -638,8 +638,9 @@ def main():
                           **{"k=%d" % kk: B.quick("llama150m", kk, n_inner=30, n_outer=20)
                              for kk in (1, 2, 4, 8)}}
         out["h_sweep"] = {"workload": "llama150m x %d workers, one timed round after a short warm-up "
-                                      "round" % args.k,
-                          **{"H=%d" % h: B.rounds("llama150m", args.k, h, pg, 1, 1, warmup_inner=5)
+                                      "round, then 19 more outer steps" % args.k,
+                          **{"H=%d" % h: B.rounds("llama150m", args.k, h, pg, 1, 1, warmup_inner=5,
+                                                  extra_outer=19)
                              for h in (50, 125)}}
         out["llama1.1b_x4"] = dict(B.quick("llama1.1b", 4, pg=D.F16, n_inner=20, n_outer=20),
                                    config="llama1.1b x 4 workers (the paper's 1.1B run), f16 "
@@ -664,7 +665,7 @@ def main():
             "zeros": B.quick("llama150m", args.k, zeros=True),
             "synthetic": B.quick("llama150m", args.k)}
         out["stream_patterns"] = B.stream_patterns()
-        out["delayed_outer"] = B.delayed_outer("llama150m", args.k, pg, 4, 10)
+        out["delayed_outer"] = B.delayed_outer("llama150m", args.k, pg, 4, 20)
         out["tiny"] = dict(B.rounds("tiny", 2, 4, D.F32, 20, 2),
                            note="0.79M parameters x 2 workers: cache-resident and launch-bound, "
                                 "reported for completeness, not roofline-meaningful")
