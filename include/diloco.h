@@ -299,6 +299,7 @@ int diloco_cast_f32_to_bf16(const float* in, uint16_t* out, uint64_t n, void* st
  *   inner_block 64|128|256, outer_block -1|64|128|256 (threads per workgroup; -1 automatic),
  *   inner_waves / outer_waves -1..32 (resident waves per CU: -1 automatic, 0 hardware maximum),
  *   outer_anyk 0|1 (1: the run-time-k kernel also for k <= 8),
+ *   snapshot_waves / update_waves / merge_waves -1..32 (the delayed outer step's three kernels),
  *   check_block 64|256, check_vec 1|2|4|8, check_waves 0..32, check_persist 0..64.
  * The defaults are the measured optimum on MI355X.  Unknown names or values return
  * DILOCO_ERR_INVALID_ARG. */

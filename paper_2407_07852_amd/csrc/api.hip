@@ -702,6 +702,9 @@ int diloco_set_tuning(diloco_ctx* ctx, const char* name, int value) {
   else if (n == "inner_waves" && value >= -1 && value <= 32) t.inner_waves = value;
   else if (n == "outer_waves" && value >= -1 && value <= 32) t.outer_waves = value;
   else if (n == "outer_anyk" && (value == 0 || value == 1)) t.outer_anyk = value;
+  else if (n == "snapshot_waves" && value >= -1 && value <= 32) t.snapshot_waves = value;
+  else if (n == "update_waves" && value >= -1 && value <= 32) t.update_waves = value;
+  else if (n == "merge_waves" && value >= -1 && value <= 32) t.merge_waves = value;
   else if (n == "check_block" && (value == 64 || value == 256)) t.check_block = value;
   else if (n == "check_vec" && (value == 1 || value == 2 || value == 4 || value == 8)) t.check_vec = value;
   else if (n == "check_waves" && value >= 0 && value <= 32) t.check_waves = value;

@@ -32,6 +32,9 @@ struct Tuning {
   int outer_block = -1;   // threads per workgroup of the outer step (64, 128 or 256): -1 = auto
   int outer_waves = -1;   // resident waves per CU for the outer step: -1 = auto, 0 = maximum
   int outer_anyk = 0;     // 1: use the run-time-k kernel for every k (comparison with the templates)
+  int snapshot_waves = -1;  // delayed outer step: resident waves per CU of its three kernels,
+  int update_waves = -1;    // -1 = automatic, 0 = hardware maximum
+  int merge_waves = -1;
   int check_block = 256;  // 64 or 256
   int check_vec = 4;      // 1, 2, 4 (8 with 64-thread blocks)
   int check_waves = 16;   // resident waves per CU (0 = hardware maximum)

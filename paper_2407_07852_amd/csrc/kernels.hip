@@ -293,7 +293,7 @@ __global__ __launch_bounds__(B) void outer_fused_anyk_kernel(const OuterArgs a, 
 // Delayed application of the outer step (the asynchronous weight averaging the paper's
 // Conclusion names as future work): snapshot at the round boundary, and the later merge
 //   theta_r <- theta0_new - (snapshot_r - theta_r),
-// which keeps what each worker did since the snapshot.  Grid = (tiles, k) for both.
+// which keeps what each worker did since the snapshot.
 // ------------------------------------------------------------------------------------------
 template <int B>
 __global__ __launch_bounds__(B) void snapshot_kernel(const float* __restrict__ theta,
@@ -304,22 +304,39 @@ __global__ __launch_bounds__(B) void snapshot_kernel(const float* __restrict__ t
   if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
+// One workgroup per tile for all k workers, so that theta0 is read once per element and not once
+// per worker: 1 + 2k read streams and k write streams, (4 + 12k) B per element.  Workers go in
+// batches of up to 8 (16 loads in flight per lane beside theta0).
 template <int B>
 __global__ __launch_bounds__(B) void merge_delayed_kernel(const float* __restrict__ theta0,
                                                           const float* __restrict__ snap,
                                                           float* __restrict__ theta, uint64_t stride,
-                                                          uint32_t tiles) {
+                                                          int k, uint32_t tiles) {
+  constexpr int kBatch = 8;
   const size_t e = (size_t)blockIdx.x * B + threadIdx.x;
-  const size_t i = (size_t)blockIdx.y * (stride / kVecElems) + e;
+  const size_t rstride = stride / kVecElems;
+  const f32x4* __restrict__ sg_p = reinterpret_cast<const f32x4*>(snap) + e;
+  f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(theta) + e;
   const f32x4 t0 = ld<true>(reinterpret_cast<const f32x4*>(theta0) + e);
-  const f32x4 sg = ld<true>(reinterpret_cast<const f32x4*>(snap) + i);
-  f32x4 th = ld<true>(reinterpret_cast<f32x4*>(theta) + i);
+  for (int r0 = 0; r0 < k; r0 += kBatch) {
+    f32x4 sg[kBatch], th[kBatch];
 #pragma unroll
-  for (int c = 0; c < kVecElems; ++c) {
-    const float since_snapshot = sg[c] - th[c];
-    th[c] = t0[c] - since_snapshot;
+    for (int j = 0; j < kBatch; ++j)
+      if (r0 + j < k) {
+        sg[j] = ld<true>(sg_p + (size_t)(r0 + j) * rstride);
+        th[j] = ld<true>(th_p + (size_t)(r0 + j) * rstride);
+      }
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j)
+      if (r0 + j < k) {
+#pragma unroll
+        for (int c = 0; c < kVecElems; ++c) {
+          const float since_snapshot = sg[j][c] - th[j][c];
+          th[j][c] = t0[c] - since_snapshot;
+        }
+        st<true>(th_p + (size_t)(r0 + j) * rstride, th[j]);
+      }
   }
-  st<true>(reinterpret_cast<f32x4*>(theta) + i, th);
   if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
@@ -561,12 +578,14 @@ hipError_t launch_outer(const OuterArgs& a, const Tuning& t, hipStream_t s) {
 }
 
 // The delayed update: k+2 read streams, 2 write streams; read-heavy traffic sustains more loads
-// in flight than the fused step (one more wave than the run-time-k kernel's 4).
+// in flight than the fused step (measured optimum at k = 8: 7 waves per CU against the fused
+// step's 4).  The snapshot, a plain copy with one load per wave, wants every wave slot; the
+// merge, with up to 17 loads per wave, 3 waves per CU.
 template <int PG, bool RM>
 static hipError_t launch_outer_update_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
   constexpr int B = 64;
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
-  const int waves = 5;
+  const int waves = t.update_waves >= 0 ? t.update_waves : 7;
   hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM, B, false>), dim3((uint32_t)tiles), dim3(B),
                      pad_lds_bytes(waves, B, t.lds_per_cu), s, a, (uint32_t)tiles);
   return hipGetLastError();
@@ -586,7 +605,8 @@ hipError_t launch_snapshot(const float* theta, float* snap, uint64_t stride, uin
   constexpr int B = 64;
   const uint64_t tiles = n_pad / (uint64_t)(B * kVecElems);
   hipLaunchKernelGGL(snapshot_kernel<B>, dim3((uint32_t)tiles, (uint32_t)k), dim3(B),
-                     pad_lds_bytes(16, B, t.lds_per_cu), s, theta, snap, stride, (uint32_t)tiles);
+                     pad_lds_bytes(t.snapshot_waves >= 0 ? t.snapshot_waves : 0, B, t.lds_per_cu), s,
+                     theta, snap, stride, (uint32_t)tiles);
   return hipGetLastError();
 }
 
@@ -595,9 +615,9 @@ hipError_t launch_merge_delayed(const float* theta0, const float* snap, float* t
                                 hipStream_t s) {
   constexpr int B = 64;
   const uint64_t tiles = n_pad / (uint64_t)(B * kVecElems);
-  hipLaunchKernelGGL(merge_delayed_kernel<B>, dim3((uint32_t)tiles, (uint32_t)k), dim3(B),
-                     pad_lds_bytes(14, B, t.lds_per_cu), s, theta0, snap, theta, stride,
-                     (uint32_t)tiles);
+  hipLaunchKernelGGL(merge_delayed_kernel<B>, dim3((uint32_t)tiles), dim3(B),
+                     pad_lds_bytes(t.merge_waves >= 0 ? t.merge_waves : 3, B, t.lds_per_cu), s,
+                     theta0, snap, theta, stride, k, (uint32_t)tiles);
   return hipGetLastError();
 }
 
