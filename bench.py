@@ -257,6 +257,9 @@ class Bench:
         t_sync = med(self.time_launches(dl.outer_step, reps))
         t_a = med(self.time_launches(seq_a, reps))
         t_b = med(self.time_launches(seq_b, reps))
+        halves = self.time_sequence([lambda: dl.outer_begin(snapshot=snap, side_stream=side),
+                                     dl.outer_finish] * reps)
+        t_snapshot, t_rest = med(halves[0::2]), med(halves[1::2])
         t_c = med(self.time_launches(seq_c, reps))
         dl.close()
         del dl, grads, snap
@@ -270,6 +273,10 @@ class Bench:
                 "bytes_begin_finish": bytes_delayed,
                 "begin_finish_GBps": bytes_delayed / t_b / 1e6,
                 "begin_finish_frac_of_peak": bytes_delayed / t_b / 1e6 / HBM_PEAK_GBS,
+                "snapshot_ms": t_snapshot,
+                "snapshot_frac_of_peak": 8 * k * n / t_snapshot / 1e6 / HBM_PEAK_GBS,
+                "update_plus_merge_ms": t_rest,
+                "update_plus_merge_frac_of_peak": (20 + 16 * k) * n / t_rest / 1e6 / HBM_PEAK_GBS,
                 "note": "snapshot 8k + update (16+4k) + merge (4+12k) = (20+24k) B/element against "
                         "(16+8k) for the plain outer step: on one GPU the delayed form costs more "
                         "traffic and the overlap buys little, because both streams compete for "
@@ -524,6 +531,8 @@ def main():
                     help="instead of the benchmark: allocate and free this many GiB, and time the "
                          "inner step before and for 9 s afterwards (the driver clears freed "
                          "memory in the background)")
+    ap.add_argument("--delayed-only", action="store_true",
+                    help="only the delayed outer step's leg on --workload (for counter runs)")
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MIB",
                     help="first run a plain copy kernel of this many MiB three times (reference "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -547,7 +556,8 @@ def main():
     big = synth.WORKLOADS["llama1.1b" if full else args.workload]()
     kk = max(args.k, 8) if (full or args.free_effect) else args.k
     big_lay, _ = D.diloco_query_layout(D.make_config(big.numel, kk))
-    pool_bytes = (big_lay.arena_bytes + ((kk - 1) * big_lay.stride + big_lay.n_pad) * 4
+    # (twice the gradient size: the delayed outer step's snapshot is as large as the gradients)
+    pool_bytes = (big_lay.arena_bytes + 2 * ((kk - 1) * big_lay.stride + big_lay.n_pad) * 4
                   + big_lay.n_pad + (1100 << 20))
     if args.settle > 0:
         torch.cuda.init()
@@ -566,6 +576,10 @@ def main():
 
     if args.free_effect:
         print(json.dumps({"free_effect": B.free_effect(args.free_effect)}))
+        return
+    if args.delayed_only:
+        pgd = D.F16 if (args.pg or ("f16" if args.workload == "llama1.1b" else "f32")) == "f16" else D.F32
+        print(json.dumps({"delayed_outer": B.delayed_outer(args.workload, args.k, pgd, 2, 20)}))
         return
 
     pgn = args.pg or ("f16" if args.workload == "llama1.1b" else "f32")
@@ -665,7 +679,8 @@ def main():
             "zeros": B.quick("llama150m", args.k, zeros=True),
             "synthetic": B.quick("llama150m", args.k)}
         out["stream_patterns"] = B.stream_patterns()
-        out["delayed_outer"] = B.delayed_outer("llama150m", args.k, pg, 4, 20)
+        out["delayed_outer"] = {"llama150m": B.delayed_outer("llama150m", args.k, pg, 4, 20),
+                                "llama1.1b": B.delayed_outer("llama1.1b", args.k, D.F16, 2, 20)}
         out["tiny"] = dict(B.rounds("tiny", 2, 4, D.F32, 20, 2),
                            note="0.79M parameters x 2 workers: cache-resident and launch-bound, "
                                 "reported for completeness, not roofline-meaningful")
