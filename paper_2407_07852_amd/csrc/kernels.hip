@@ -553,9 +553,10 @@ static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, hipStream_
     }
   }
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
-  // the run-time-k kernel's own optimum (measured at k = 2 ... 32): fewer waves as k grows
+  // the run-time-k kernel's own optimum (measured at k = 2 ... 32, the same in all three
+  // pseudo-gradient modes): fewer waves as k grows
   int waves = t.outer_waves;
-  if (waves < 0) waves = a.k <= 2 ? 8 : a.k <= 4 ? 6 : a.k <= 6 ? 5 : a.k <= 8 ? 4 : 3;
+  if (waves < 0) waves = a.k <= 2 ? 8 : a.k <= 4 ? 6 : a.k <= 6 ? 5 : a.k <= 11 ? 4 : 3;
   const uint32_t lds = pad_lds_bytes(waves, B, t.lds_per_cu);
   hipLaunchKernelGGL((outer_fused_anyk_kernel<PG, RM, B, true>), dim3((uint32_t)tiles), dim3(B), lds,
                      s, a, (uint32_t)tiles);
