@@ -203,8 +203,8 @@ __device__ __forceinline__ float mean_of_sum(float s, const OuterArgs& a) {
 }
 
 // B/64 waves per workgroup, each wave one 256-element tile: all K+2 loads in flight, then the
-// arithmetic, then K+2 stores.  Two waves per workgroup put 2 KiB of every stream in flight from
-// one CU at the same moment, which measured 1-2.5 points faster than single-wave workgroups.
+// arithmetic, then K+2 stores.  The library launches single-wave workgroups (B = 64); larger B
+// exists for the launch-shape sweeps.
 // RM: the average is rounded through the pseudo-gradient type as well.
 template <int K, int PG, bool RM, int B>
 __global__ __launch_bounds__(B) void outer_fused_kernel(const OuterArgs a, uint32_t tiles) {
@@ -515,7 +515,7 @@ hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const 
 // k <= 2 and lose 1-15 points from k = 3 on), and 9, 6, 6, 4, 4, 4, 5, 4 waves for k = 1..8.  The
 // reduced-precision modes' conversions lengthen each wave's compute phase, which at k = 2, 4, 5
 // wants one more wave.  One wave off the optimum costs 0.5-5 points.  The run-time-k kernel
-// (k >= 9) holds up to 16 workers' loads per wave and wants 4.
+// (k >= 9) has a rule of its own at its launch.
 struct OuterShape { int block, waves; };
 static OuterShape outer_shape(const Tuning& t, int k, int pg) {
   static const int kWaves32[9] = {0, 9, 6, 6, 4, 4, 4, 5, 4};
