@@ -98,7 +98,7 @@ class Bench:
                 grp[-2] = 2
             dl.set_param_groups(grp, [1.0, 1.0, 0.5], [0.1, 0.0, 0.0])
         gdt = torch.float16 if g16 else torch.float32
-        grads = dl.new_grads(gdt, out=self.take(dl.grads_numel() * (2 if g16 else 4), gdt))
+        grads = dl.new_grads(gdt)   # the arena's own gradient slots
         for r in range(k):
             if g16:
                 synth.device_fill_f16(grads[r].data_ptr(), dl.layout.n_pad,
@@ -550,15 +550,15 @@ def main():
     import synth
     torch.cuda.set_device(0)
     tune = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.tune}
-    # one device allocation for the whole run, sized for the largest leg (arena + FP32 gradients
-    # + the generator's kind map), the placement legs' largest offset and alignment slack
+    # one device allocation for the whole run, sized for the largest leg (arena, which includes
+    # the FP32 gradient slots, + the generator's kind map), the placement legs' largest offset
+    # and alignment slack
     full = not args.no_also and args.workload == "llama150m" and not args.free_effect
     big = synth.WORKLOADS["llama1.1b" if full else args.workload]()
     kk = max(args.k, 8) if (full or args.free_effect) else args.k
     big_lay, _ = D.diloco_query_layout(D.make_config(big.numel, kk))
-    # (twice the gradient size: the delayed outer step's snapshot is as large as the gradients)
-    pool_bytes = (big_lay.arena_bytes + 2 * ((kk - 1) * big_lay.stride + big_lay.n_pad) * 4
-                  + big_lay.n_pad + (1100 << 20))
+    # (the arena holds the gradients; the delayed outer step's snapshot is k slots more)
+    pool_bytes = (big_lay.arena_bytes + kk * big_lay.slot * 4 + big_lay.n_pad + (1100 << 20))
     if args.settle > 0:
         torch.cuda.init()
         time.sleep(args.settle)

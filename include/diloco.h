@@ -12,11 +12,13 @@
  * Here all k replicas live on ONE GPU in a single caller-owned arena of flat, padded
  * multi-tensor buffers, and each step is one fused streaming kernel:
  *
- *   arena (FP32):  theta0[stride]  mom[stride]  theta[k][stride]  m[k][stride]  v[k][stride]
- *   (n_pad <= stride elements of each buffer are used)
+ *   arena (FP32 slots):  theta0  mom  theta[k]  m[k]  v[k]  grads[k]     (buffer-major), or
+ *                        theta0  mom  { theta_r  m_r  v_r  grads_r } x k  (worker-major)
+ *   (n_pad <= slot elements of each buffer are used; see diloco_layout)
  *
  * theta0 = outer weights theta(t); mom = outer momentum buffer; theta/m/v = each worker's
- * weights and AdamW moments.  Every tensor of the parameter list starts at a multiple of 64
+ * weights and AdamW moments; grads = a place for each worker's gradients next to its state
+ * (a caller may use it or pass its own buffer).  Every tensor of the parameter list starts at a multiple of 64
  * elements inside each buffer; the gaps and the tail up to n_pad hold zeros, and stay zero as
  * long as the gradient buffers hold zeros there too (both steps map 0 to 0).
  *
@@ -62,7 +64,14 @@ enum { /* diloco_get_buffer selector */
   DILOCO_BUF_MOM = 1,    /* outer Nesterov momentum buffer, [n_pad] */
   DILOCO_BUF_THETA = 2,  /* worker weights, replica r at + r*stride */
   DILOCO_BUF_M = 3,      /* AdamW first moment */
-  DILOCO_BUF_V = 4       /* AdamW second moment */
+  DILOCO_BUF_V = 4,      /* AdamW second moment */
+  DILOCO_BUF_GRADS = 5   /* the arena's gradient slot of replica r (FP32-sized; see diloco_layout) */
+};
+
+enum { /* diloco_config.layout_mode: order of the flat buffers inside the arena */
+  DILOCO_LAYOUT_AUTO = 0,         /* by buffer size, see diloco_layout */
+  DILOCO_LAYOUT_BUFFER_MAJOR = 1, /* theta0, mom, theta[k], m[k], v[k], grads[k] */
+  DILOCO_LAYOUT_WORKER_MAJOR = 2  /* theta0, mom, then per worker: theta_r, m_r, v_r, grads_r */
 };
 
 #define DILOCO_MAX_WORKERS 64
@@ -97,13 +106,32 @@ typedef struct {
                                best bandwidth); unused by query_layout */
   uint64_t arena_bytes;
   void* stream;             /* hipStream_t, borrowed; NULL = the default stream */
+  int32_t layout_mode;      /* DILOCO_LAYOUT_*; 0 = automatic */
+  int32_t reserved;         /* 0 */
 } diloco_config;
 
+/* Where the flat buffers lie in the arena.  Every buffer occupies one slot of `slot` elements
+ * (n_pad rounded up to 2 MiB); replica r of theta, m, v and of the arena's gradient slots
+ * starts r*stride elements after replica 0.
+ *   buffer-major: stride = slot; theta0, mom, theta[0..k), m[0..k), v[0..k), grads[0..k).
+ *   worker-major: stride = 4*slot; theta0, mom, then theta_r, m_r, v_r, grads_r per worker.
+ * The automatic choice is worker-major when 4*slot*4 bytes lies between 10 and 24 GiB (about
+ * 0.7 to 1.6 billion parameters per replica), buffer-major otherwise: measured on MI355X, the
+ * outer step sustains most when consecutive workers' weights lie 12-20 GiB apart (or directly
+ * adjacent, when they are small), and the inner step when a worker's four streams are
+ * adjacent.  Results never depend on the mode.
+ * The gradient slots are FP32-sized; a caller may write gradients there (FP32: [k] rows of
+ * n_pad floats, `stride` floats apart; binary16: rows of n_pad halves, 2*stride halves apart)
+ * or pass any other device buffer to diloco_inner_step. */
 typedef struct {
   uint64_t n_pad;       /* padded elements per flat buffer (multiple of DILOCO_TILE) */
-  uint64_t stride;      /* elements between consecutive replicas of theta / m / v */
+  uint64_t stride;      /* elements between consecutive replicas of theta / m / v / grads */
   uint64_t arena_bytes; /* bytes the arena must provide */
   uint64_t off_theta0, off_mom, off_theta, off_m, off_v; /* byte offsets inside the arena */
+  uint64_t off_grads;   /* byte offset of replica 0's gradient slot */
+  uint64_t slot;        /* elements per buffer slot (>= n_pad) */
+  int32_t layout_mode;  /* the mode in effect: DILOCO_LAYOUT_BUFFER_MAJOR or _WORKER_MAJOR */
+  int32_t reserved;
 } diloco_layout;
 
 /* Flat layout for cfg's tensor list and k (host only, touches no GPU): the per-tensor iteration
@@ -262,9 +290,9 @@ int diloco_outer_step(diloco_ctx* ctx);
  *                        carries each worker's progress since the snapshot over to the new
  *                        outer weights.
  * With no inner step in between, the pair equals diloco_outer_step bit for bit (finite weights).
- * snapshot: device, caller-owned, [k][stride] floats laid out like the worker weights
- * (snapshot_bytes >= ((k-1)*stride + n_pad)*4), 16-byte aligned, untouched by the caller until
- * diloco_outer_finish has run.  side_stream: hipStream_t of the same device (default priority);
+ * snapshot: device, caller-owned, k rows of n_pad floats, `slot` floats apart (dense, whatever
+ * the arena's layout mode; snapshot_bytes >= ((k-1)*slot + n_pad)*4), 16-byte aligned, untouched
+ * by the caller until diloco_outer_finish has run.  side_stream: hipStream_t of the same device (default priority);
  * it may be the context's own stream, in which case nothing overlaps.  Between begin and finish
  * theta0 and mom are in flux: diloco_outer_step and a second diloco_outer_begin return
  * DILOCO_ERR_STATE, and so does diloco_outer_finish without a begin.  begin enqueues two

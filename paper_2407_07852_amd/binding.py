@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(HERE, "libdiloco_hip.so")
 OK, ROUND_COMPLETE = 0, 1
 ERR_INVALID_ARG, ERR_ALIGN, ERR_ARENA_TOO_SMALL, ERR_HIP, ERR_STATE = -1, -2, -3, -4, -5
 F32, F16, BF16 = 0, 1, 2
-BUF_THETA0, BUF_MOM, BUF_THETA, BUF_M, BUF_V = 0, 1, 2, 3, 4
+BUF_THETA0, BUF_MOM, BUF_THETA, BUF_M, BUF_V, BUF_GRADS = 0, 1, 2, 3, 4, 5
+LAYOUT_AUTO, LAYOUT_BUFFER_MAJOR, LAYOUT_WORKER_MAJOR = 0, 1, 2
 MAX_WORKERS, TENSOR_ALIGN, TILE, MAX_GROUPS = 64, 64, 8192, 8
 
 EXPORTS = ["diloco_query_layout", "diloco_init", "diloco_unscale_check", "diloco_inner_step",
@@ -31,12 +32,14 @@ class Config(C.Structure):
                 ("eps", C.c_double), ("weight_decay", C.c_double),
                 ("outer_lr", C.c_double), ("outer_momentum", C.c_double),
                 ("pg_dtype", C.c_int32), ("pg_round_mean", C.c_int32), ("arena", C.c_void_p), ("arena_bytes", C.c_uint64),
-                ("stream", C.c_void_p)]
+                ("stream", C.c_void_p), ("layout_mode", C.c_int32), ("reserved", C.c_int32)]
 
 
 class Layout(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("n_pad", "stride", "arena_bytes", "off_theta0",
-                                          "off_mom", "off_theta", "off_m", "off_v")]
+                                          "off_mom", "off_theta", "off_m", "off_v", "off_grads",
+                                          "slot")] + \
+               [("layout_mode", C.c_int32), ("reserved", C.c_int32)]
 
 
 class InnerCall(C.Structure):
@@ -105,11 +108,11 @@ def _check(rc, ctx=None):
 
 def make_config(numel, k_workers, h_inner_steps=0, inner_lr=4e-4, beta1=0.9, beta2=0.999,
                 eps=1e-8, weight_decay=0.1, outer_lr=0.7, outer_momentum=0.9, pg_dtype=F32,
-                pg_round_mean=0, arena=None, arena_bytes=0, stream=None):
+                pg_round_mean=0, arena=None, arena_bytes=0, stream=None, layout_mode=0):
     arr = (C.c_uint64 * len(numel))(*[int(n) for n in numel])
     cfg = Config(len(numel), C.cast(arr, C.POINTER(C.c_uint64)), k_workers, h_inner_steps,
                  inner_lr, beta1, beta2, eps, weight_decay, outer_lr, outer_momentum, pg_dtype,
-                 int(pg_round_mean), arena, arena_bytes, stream)
+                 int(pg_round_mean), arena, arena_bytes, stream, int(layout_mode), 0)
     cfg._keep = arr
     return cfg
 
@@ -260,21 +263,32 @@ class DiLoCo:
         return torch.as_strided(flat, (reps, L.n_pad), (L.stride, 1))
 
     def grads_numel(self):
-        """Elements of a gradient buffer whose replicas are spaced like the arena's."""
-        return (self.k - 1) * self.layout.stride + self.layout.n_pad
+        """Elements of a dense [k][slot] buffer (a gradient buffer outside the arena, or the
+        delayed outer step's snapshot)."""
+        return (self.k - 1) * self.layout.slot + self.layout.n_pad
+
+    def arena_grads(self, dtype=torch.float32):
+        """The arena's own gradient slots as a [k][n_pad] view of the given dtype (float32 or
+        float16): next to each worker's state in the worker-major layout, after the moments in
+        the buffer-major one.  Not cleared."""
+        L = self.layout
+        if dtype == torch.float32:
+            return torch.as_strided(self.arena, (self.k, L.n_pad), (L.stride, 1), L.off_grads // 4)
+        assert dtype == torch.float16
+        return torch.as_strided(self.arena.view(torch.float16), (self.k, L.n_pad),
+                                (2 * L.stride, 1), L.off_grads // 2)
 
     def new_grads(self, dtype=torch.float32, out=None):
-        """A zeroed gradient buffer [k][n_pad] of the given dtype, replicas spaced like the
-        arena's (stride elements apart) so that all streams of a tile share their alignment.
-        out: optional 1-D device tensor of that dtype with at least grads_numel() elements to
-        use instead of a new allocation."""
+        """A zeroed gradient buffer [k][n_pad] of the given dtype.  By default the arena's own
+        gradient slots (every call returns the same memory); with out, a 1-D device tensor of
+        that dtype with at least grads_numel() elements, dense rows `slot` elements apart in
+        it."""
         L = self.layout
         if out is None:
-            flat = torch.zeros(self.grads_numel(), dtype=dtype, device=self.device)
-        else:
-            assert out.dtype == dtype and out.numel() >= self.grads_numel()
-            flat = out[:self.grads_numel()].zero_()
-        return torch.as_strided(flat, (self.k, L.n_pad), (L.stride, 1))
+            return self.arena_grads(dtype).zero_()
+        assert out.dtype == dtype and out.numel() >= self.grads_numel()
+        flat = out[:self.grads_numel()].zero_()
+        return torch.as_strided(flat, (self.k, L.n_pad), (L.slot, 1))
 
     def new_flags(self):
         return torch.zeros(self.k, dtype=torch.int32, device=self.device)

@@ -79,13 +79,14 @@ hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const 
 hipError_t launch_outer(const OuterArgs& a, const Tuning& t, hipStream_t s);
 // Delayed application of the outer step: copy of every worker's weights into the snapshot; the
 // outer update computed from the snapshot (a.theta = snapshot; theta0 and mom updated, no
-// broadcast); and theta_r <- theta0 - (snapshot_r - theta_r).
-hipError_t launch_snapshot(const float* theta, float* snap, uint64_t stride, uint64_t n_pad, int k,
-                           const Tuning& t, hipStream_t s);
+// broadcast); and theta_r <- theta0 - (snapshot_r - theta_r).  The snapshot's rows are
+// snap_stride elements apart, the workers' weights stride.
+hipError_t launch_snapshot(const float* theta, float* snap, uint64_t stride, uint64_t snap_stride,
+                           uint64_t n_pad, int k, const Tuning& t, hipStream_t s);
 hipError_t launch_outer_update(const OuterArgs& a, const Tuning& t, hipStream_t s);
 hipError_t launch_merge_delayed(const float* theta0, const float* snap, float* theta,
-                                uint64_t stride, uint64_t n_pad, int k, const Tuning& t,
-                                hipStream_t s);
+                                uint64_t stride, uint64_t snap_stride, uint64_t n_pad, int k,
+                                const Tuning& t, hipStream_t s);
 hipError_t launch_check(const void* g, uint64_t g_stride, uint64_t n_pad, int k, bool g16,
                         int32_t* found_inf, const Tuning& t, int n_cu, hipStream_t s);
 hipError_t launch_init_state(float* theta0, float* mom, float* theta, float* m, float* v,

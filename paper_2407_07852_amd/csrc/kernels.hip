@@ -298,9 +298,11 @@ __global__ __launch_bounds__(B) void outer_fused_anyk_kernel(const OuterArgs a, 
 template <int B>
 __global__ __launch_bounds__(B) void snapshot_kernel(const float* __restrict__ theta,
                                                      float* __restrict__ snap, uint64_t stride,
-                                                     uint32_t tiles) {
-  const size_t i = (size_t)blockIdx.y * (stride / kVecElems) + (size_t)blockIdx.x * B + threadIdx.x;
-  st<true>(reinterpret_cast<f32x4*>(snap) + i, ld<true>(reinterpret_cast<const f32x4*>(theta) + i));
+                                                     uint64_t snap_stride, uint32_t tiles) {
+  const size_t e = (size_t)blockIdx.x * B + threadIdx.x;
+  const size_t i = (size_t)blockIdx.y * (stride / kVecElems) + e;
+  const size_t j = (size_t)blockIdx.y * (snap_stride / kVecElems) + e;
+  st<true>(reinterpret_cast<f32x4*>(snap) + j, ld<true>(reinterpret_cast<const f32x4*>(theta) + i));
   if (tiles == 0xffffffffu) occupancy_pad[threadIdx.x] = 0.f;  // never true: keeps the LDS pad
 }
 
@@ -311,10 +313,11 @@ template <int B>
 __global__ __launch_bounds__(B) void merge_delayed_kernel(const float* __restrict__ theta0,
                                                           const float* __restrict__ snap,
                                                           float* __restrict__ theta, uint64_t stride,
-                                                          int k, uint32_t tiles) {
+                                                          uint64_t snap_stride, int k,
+                                                          uint32_t tiles) {
   constexpr int kBatch = 8;
   const size_t e = (size_t)blockIdx.x * B + threadIdx.x;
-  const size_t rstride = stride / kVecElems;
+  const size_t rstride = stride / kVecElems, sstride = snap_stride / kVecElems;
   const f32x4* __restrict__ sg_p = reinterpret_cast<const f32x4*>(snap) + e;
   f32x4* __restrict__ th_p = reinterpret_cast<f32x4*>(theta) + e;
   const f32x4 t0 = ld<true>(reinterpret_cast<const f32x4*>(theta0) + e);
@@ -323,7 +326,7 @@ __global__ __launch_bounds__(B) void merge_delayed_kernel(const float* __restric
 #pragma unroll
     for (int j = 0; j < kBatch; ++j)
       if (r0 + j < k) {
-        sg[j] = ld<true>(sg_p + (size_t)(r0 + j) * rstride);
+        sg[j] = ld<true>(sg_p + (size_t)(r0 + j) * sstride);
         th[j] = ld<true>(th_p + (size_t)(r0 + j) * rstride);
       }
 #pragma unroll
@@ -604,24 +607,24 @@ hipError_t launch_outer_update(const OuterArgs& a, const Tuning& t, hipStream_t 
   }
 }
 
-hipError_t launch_snapshot(const float* theta, float* snap, uint64_t stride, uint64_t n_pad, int k,
-                           const Tuning& t, hipStream_t s) {
+hipError_t launch_snapshot(const float* theta, float* snap, uint64_t stride, uint64_t snap_stride,
+                           uint64_t n_pad, int k, const Tuning& t, hipStream_t s) {
   constexpr int B = 64;
   const uint64_t tiles = n_pad / (uint64_t)(B * kVecElems);
   hipLaunchKernelGGL(snapshot_kernel<B>, dim3((uint32_t)tiles, (uint32_t)k), dim3(B),
                      pad_lds_bytes(t.snapshot_waves >= 0 ? t.snapshot_waves : 0, B, t.lds_per_cu), s,
-                     theta, snap, stride, (uint32_t)tiles);
+                     theta, snap, stride, snap_stride, (uint32_t)tiles);
   return hipGetLastError();
 }
 
 hipError_t launch_merge_delayed(const float* theta0, const float* snap, float* theta,
-                                uint64_t stride, uint64_t n_pad, int k, const Tuning& t,
-                                hipStream_t s) {
+                                uint64_t stride, uint64_t snap_stride, uint64_t n_pad, int k,
+                                const Tuning& t, hipStream_t s) {
   constexpr int B = 64;
   const uint64_t tiles = n_pad / (uint64_t)(B * kVecElems);
   hipLaunchKernelGGL(merge_delayed_kernel<B>, dim3((uint32_t)tiles), dim3(B),
                      pad_lds_bytes(t.merge_waves >= 0 ? t.merge_waves : 3, B, t.lds_per_cu), s,
-                     theta0, snap, theta, stride, k, (uint32_t)tiles);
+                     theta0, snap, theta, stride, snap_stride, k, (uint32_t)tiles);
   return hipGetLastError();
 }
 

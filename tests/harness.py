@@ -22,9 +22,9 @@ def oracle_layout(wl):
 class GpuSide:
     """The HIP library on the workload, inputs generated on the device."""
 
-    def __init__(self, wl, k, pg_f16=False, hp=None, h=0, round_mean=False):
+    def __init__(self, wl, k, pg_f16=False, hp=None, h=0, round_mean=False, layout_mode=0):
         """pg_f16: False (FP32), True (FP16) or an oracle.PG_* code (the library uses the same
-        numbering)."""
+        numbering).  layout_mode: the library's DILOCO_LAYOUT_* (0 = automatic)."""
         import torch
         import paper_2407_07852_amd as D
         self.torch, self.D, self.wl, self.k = torch, D, wl, k
@@ -39,7 +39,8 @@ class GpuSide:
                                   stream=torch.cuda.current_stream().cuda_stream)
 
         self.dl = D.DiLoCo(wl.numel, k, fill_theta0=fill, h_inner_steps=h,
-                           pg_dtype=oracle._pg_code(pg_f16), pg_round_mean=int(round_mean), **hp)
+                           pg_dtype=oracle._pg_code(pg_f16), pg_round_mean=int(round_mean),
+                           layout_mode=layout_mode, **hp)
         self.n_pad = self.dl.layout.n_pad
         self.grads = None
 

@@ -155,6 +155,46 @@ def test_lr_argument_and_zero_lr():
     gpu.dl.close()
 
 
+def test_layout_modes_give_identical_results_and_accessors_agree():
+    """The same rounds (FP16 gradients with a skipped worker, FP16 pseudo-gradient, one plain and
+    one delayed outer step) in the buffer-major and the worker-major arena: every buffer bitwise
+    equal; the accessors return the addresses the layout describes."""
+    import torch
+    import paper_2407_07852_amd as D
+    wl = _ragged(40)
+    k = 5
+    sides = [GpuSide(wl, k, True, layout_mode=mode) for mode in (D.LAYOUT_BUFFER_MAJOR,
+                                                                 D.LAYOUT_WORKER_MAJOR)]
+    for side, mode in zip(sides, (D.LAYOUT_BUFFER_MAJOR, D.LAYOUT_WORKER_MAJOR)):
+        L = side.dl.layout
+        assert L.layout_mode == mode
+        base = side.dl.arena.data_ptr()
+        for which, off in ((D.BUF_THETA, L.off_theta), (D.BUF_M, L.off_m), (D.BUF_V, L.off_v),
+                           (D.BUF_GRADS, L.off_grads)):
+            for r in (0, k - 1):
+                assert D.diloco_get_buffer(side.dl.ctx, which, r) == base + off + r * L.stride * 4
+        assert side.dl.arena_grads().data_ptr() == base + L.off_grads
+        flags = side.dl.new_flags()
+        for step in range(3):
+            g = side.gen_grads(step, f16=True, inject_replica=2 if step == 1 else None,
+                               inject_period=97)
+            side.dl.unscale_check(g, 1.0 / 65536, flags)
+            side.dl.inner_step(g, flags=flags)
+        side.dl.outer_step()
+        side.dl.inner_step(side.gen_grads(3))
+        side.dl.outer_begin()
+        side.dl.inner_step(side.gen_grads(4))
+        side.dl.outer_finish()
+        torch.cuda.synchronize()
+    a, b = sides
+    assert a.dl.steps() == b.dl.steps() == [5, 5, 4, 5, 5]
+    for name in ("theta0", "mom", "theta", "m", "v"):
+        x, y = getattr(a.dl, name), getattr(b.dl, name)
+        assert torch.equal(x.contiguous().view(torch.int32), y.contiguous().view(torch.int32)), name
+    for side in sides:
+        side.dl.close()
+
+
 def test_error_paths():
     import torch
     import paper_2407_07852_amd as D

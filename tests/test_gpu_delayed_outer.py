@@ -15,10 +15,12 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("pg,round_mean", [(False, False), (True, False), (oracle.PG_BF16, True)])
-@pytest.mark.parametrize("k,delay", [(2, 0), (3, 1), (8, 3), (11, 2)])
-def test_delayed_round_matches_oracle(k, delay, pg, round_mean):
+@pytest.mark.parametrize("k,delay,layout_mode", [(2, 0, 1), (3, 1, 2), (8, 3, 1), (8, 2, 2),
+                                                 (11, 2, 2)])
+def test_delayed_round_matches_oracle(k, delay, layout_mode, pg, round_mean):
     wl = synth.Workload("ragged", [(300, 257), (4097,), (1,), (64, 64), (70001,)])
-    gpu, cpu = GpuSide(wl, k, pg, round_mean=round_mean), CpuSide(wl, k, pg, round_mean=round_mean)
+    gpu = GpuSide(wl, k, pg, round_mean=round_mean, layout_mode=layout_mode)
+    cpu = CpuSide(wl, k, pg, round_mean=round_mean)
     step = 0
     for rnd in range(2):
         for _ in range(2):
@@ -44,7 +46,7 @@ def test_delayed_round_matches_oracle(k, delay, pg, round_mean):
 
 def test_no_delay_equals_the_plain_outer_step():
     wl = synth.tiny()
-    a, b = GpuSide(wl, 4, True), GpuSide(wl, 4, True)
+    a, b = GpuSide(wl, 4, True, layout_mode=1), GpuSide(wl, 4, True, layout_mode=2)
     for step in range(3):
         a.dl.inner_step(a.gen_grads(step))
         b.dl.inner_step(b.gen_grads(step))

@@ -12,14 +12,14 @@ from harness import CpuSide, GpuSide, compare, compare_state
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("n_inner", [2, 3])
-def test_captured_inner_steps_replay_correctly(n_inner):
+@pytest.mark.parametrize("n_inner,layout_mode", [(2, 1), (3, 1), (3, 2)])
+def test_captured_inner_steps_replay_correctly(n_inner, layout_mode):
     import torch
     wl = synth.tiny()
     k = 2
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
-        gpu = GpuSide(wl, k, True)          # the context borrows the capturing stream
+        gpu = GpuSide(wl, k, True, layout_mode=layout_mode)  # the context borrows the capturing stream
         g = gpu.gen_grads(0)
         flags = gpu.dl.new_flags()
     side.synchronize()

@@ -59,14 +59,15 @@ def test_stress_unscale_check_and_skip():
     gpu.dl.close()
 
 
-def test_flag_positions_brute_force():
+@pytest.mark.parametrize("layout_mode", [1, 2])
+def test_flag_positions_brute_force(layout_mode):
     """One special value at chosen positions of small ragged tensor lists: first/last element of
     a tensor, element before a pad, last real element; both gradient types."""
     torch = pytest.importorskip("torch")
     import paper_2407_07852_amd as D
     numel = [1, 63, 64, 65, 4096, 7, 1000]
     k = 3
-    dl = D.DiLoCo(numel, k, fill_theta0=lambda t, lay, off: t.zero_())
+    dl = D.DiLoCo(numel, k, fill_theta0=lambda t, lay, off: t.zero_(), layout_mode=layout_mode)
     flags = dl.new_flags()
     positions = []
     for off, n in zip(dl.offsets, numel):

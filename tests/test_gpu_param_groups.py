@@ -42,15 +42,15 @@ def test_tiny_with_groups_and_schedule():
     gpu.dl.close()
 
 
-@pytest.mark.parametrize("f16_grads", [False, True])
-def test_ragged_tensors_many_groups(f16_grads):
+@pytest.mark.parametrize("f16_grads,layout_mode", [(False, 1), (True, 1), (True, 2)])
+def test_ragged_tensors_many_groups(f16_grads, layout_mode):
     """40 tiny tensors (1..4096 elements, several inside one 256-element tile), 8 groups."""
     wl = synth.Workload("ragged40", [(s,) if j % 3 else (1, s)
                                      for j, s in enumerate(synth.ragged_sizes(40))])
     grp = [(7 * j + 3) % 8 for j in range(40)]
     lr_scale = [1.0, 0.5, 2.0, 0.0, 1.5, 0.25, 3.0, 1.0]
     wd = [0.1, 0.0, 0.3, 0.5, 0.0, 1.0, 0.01, 0.2]
-    gpu, cpu = GpuSide(wl, 3), CpuSide(wl, 3)
+    gpu, cpu = GpuSide(wl, 3, layout_mode=layout_mode), CpuSide(wl, 3)
     gpu.set_groups(grp, lr_scale, wd)
     cpu.set_groups(grp, lr_scale, wd)
     flags = gpu.dl.new_flags()

@@ -9,10 +9,11 @@ from harness import CpuSide, GpuSide, compare, compare_state, STEP_RTOL, STEP_AT
 pytestmark = pytest.mark.gpu
 
 
+@pytest.mark.parametrize("layout_mode", [1, 2])   # buffer-major, worker-major
 @pytest.mark.parametrize("pg_f16", [False, True])
-def test_tiny_round(pg_f16):
+def test_tiny_round(pg_f16, layout_mode):
     wl = synth.tiny()
-    gpu, cpu = GpuSide(wl, 2, pg_f16, h=4), CpuSide(wl, 2, pg_f16)
+    gpu, cpu = GpuSide(wl, 2, pg_f16, h=4, layout_mode=layout_mode), CpuSide(wl, 2, pg_f16)
     assert gpu.n_pad == cpu.n_pad and list(gpu.dl.offsets) == [int(o) for o in cpu.offsets]
     assert compare("theta0 init", gpu.host(gpu.dl.theta0), cpu.o.theta0, 0, 0) == 0
     assert compare_state(gpu, cpu, 0, 0) == 0

@@ -50,18 +50,44 @@ def test_layout_agrees_with_oracle_planner():
         cases.append(rng.integers(1, 20000, size=int(rng.integers(1, 60))).astype(np.uint64))
     for numel in cases:
         k = int(rng.integers(1, 9))
-        lay, offs = D.diloco_query_layout(D.make_config(numel, k))
-        want_off, want_pad = oracle.plan_layout(numel, D.TENSOR_ALIGN, D.TILE)
-        assert offs == [int(o) for o in want_off] and lay.n_pad == want_pad
-        assert lay.stride >= lay.n_pad and (lay.stride * 4) % (2 << 20) == 0
-        assert lay.stride - lay.n_pad < (2 << 20) // 4
-        # buffers in order, none overlapping, arena covers the last one
-        starts = [lay.off_theta0, lay.off_mom, lay.off_theta, lay.off_m, lay.off_v]
-        sizes = [lay.stride * 4, lay.stride * 4] + [k * lay.stride * 4] * 3
-        for i in range(4):
-            assert starts[i] + sizes[i] <= starts[i + 1]
-        assert starts[4] + sizes[4] <= lay.arena_bytes
-        assert all(s % 256 == 0 for s in starts)
+        for mode in (D.LAYOUT_AUTO, D.LAYOUT_BUFFER_MAJOR, D.LAYOUT_WORKER_MAJOR):
+            lay, offs = D.diloco_query_layout(D.make_config(numel, k, layout_mode=mode))
+            want_off, want_pad = oracle.plan_layout(numel, D.TENSOR_ALIGN, D.TILE)
+            assert offs == [int(o) for o in want_off] and lay.n_pad == want_pad
+            assert lay.slot >= lay.n_pad and (lay.slot * 4) % (2 << 20) == 0
+            assert lay.slot - lay.n_pad < (2 << 20) // 4
+            assert lay.layout_mode in (D.LAYOUT_BUFFER_MAJOR, D.LAYOUT_WORKER_MAJOR)
+            if mode != D.LAYOUT_AUTO:
+                assert lay.layout_mode == mode
+            assert lay.stride == (4 * lay.slot if lay.layout_mode == D.LAYOUT_WORKER_MAJOR
+                                  else lay.slot)
+            # all 2 + 4k buffers: 256-byte aligned, pairwise disjoint, inside the arena
+            starts = [lay.off_theta0, lay.off_mom]
+            for off in (lay.off_theta, lay.off_m, lay.off_v, lay.off_grads):
+                starts += [off + r * lay.stride * 4 for r in range(k)]
+            assert all(s % 256 == 0 for s in starts)
+            ordered = sorted(starts)
+            assert len(set(ordered)) == 2 + 4 * k
+            assert all(b - a >= lay.slot * 4 for a, b in zip(ordered, ordered[1:]))
+            assert ordered[-1] + lay.slot * 4 <= lay.arena_bytes == (2 + 4 * k) * lay.slot * 4
+            if lay.layout_mode == D.LAYOUT_WORKER_MAJOR:   # a worker's four buffers are adjacent
+                assert (lay.off_m - lay.off_theta == lay.off_v - lay.off_m
+                        == lay.off_grads - lay.off_v == lay.slot * 4)
+
+
+def test_automatic_layout_choice_by_buffer_size():
+    """Worker-major exactly when four slots span 10 to 24 GiB (the 1.1B set: 4.1 GiB slots)."""
+    D = _D()
+    gib = 1 << 30
+    for n, want in ((787456, D.LAYOUT_BUFFER_MAJOR), (234119168, D.LAYOUT_BUFFER_MAJOR),
+                    (10 * gib // 16 - 524288, D.LAYOUT_BUFFER_MAJOR),
+                    (10 * gib // 16, D.LAYOUT_WORKER_MAJOR),
+                    (1100046336, D.LAYOUT_WORKER_MAJOR), (24 * gib // 16, D.LAYOUT_WORKER_MAJOR),
+                    (24 * gib // 16 + 1, D.LAYOUT_BUFFER_MAJOR), (1 << 32, D.LAYOUT_BUFFER_MAJOR)):
+        lay, _ = D.diloco_query_layout(D.make_config([n], 4))
+        assert lay.layout_mode == want, (n, lay.layout_mode)
+    with pytest.raises(D.DilocoError):
+        D.diloco_query_layout(D.make_config([4], 2, layout_mode=3))
 
 
 def test_known_workload_sizes():

@@ -23,9 +23,9 @@ def one_case(torch, D, numel, k, steps, flagged, seed):
     ref = D.DiLoCo(numel, k, fill_theta0=lambda t, lay, off: t.normal_(0, 0.02, generator=gen), **HP)
     L = ref.layout
     # the candidate's own buffers, laid out like the arena's worker sections
-    span = (k - 1) * L.stride + L.n_pad
+    span = (k - 1) * L.slot + L.n_pad
     cand = [torch.zeros(span, dtype=torch.float32, device="cuda") for _ in range(3)]
-    views = [torch.as_strided(c, (k, L.n_pad), (L.stride, 1)) for c in cand]
+    views = [torch.as_strided(c, (k, L.n_pad), (L.slot, 1)) for c in cand]
     views[0].copy_(ref.theta)
     state = fresh_state(torch, k)
     grads = ref.new_grads()
@@ -41,7 +41,7 @@ def one_case(torch, D, numel, k, steps, flagged, seed):
             assert flags.cpu().tolist() == [int(r == flagged) for r in range(k)]
         ref.inner_step(grads, lr=lr, flags=flags if use_flags else None)
         D.diloco_inner_step_noalloc(
-            theta=cand[0].data_ptr(), m=cand[1].data_ptr(), v=cand[2].data_ptr(), stride=L.stride,
+            theta=cand[0].data_ptr(), m=cand[1].data_ptr(), v=cand[2].data_ptr(), stride=L.slot,
             n_pad=L.n_pad, k_workers=k, grad_dtype=D.F32, grads=grads.data_ptr(),
             grad_stride=grads.stride(0), inv_scale=0.5 if use_flags else 1.0,
             found_inf=flags.data_ptr() if use_flags else None, step_state=state.data_ptr(),
@@ -73,9 +73,9 @@ def test_noalloc_with_binary16_gradients_and_flags():
     gen = torch.Generator(device="cuda").manual_seed(9)
     ref = D.DiLoCo(numel, k, fill_theta0=lambda t, lay, off: t.normal_(0, 0.02, generator=gen), **HP)
     L = ref.layout
-    span = (k - 1) * L.stride + L.n_pad
+    span = (k - 1) * L.slot + L.n_pad
     cand = [torch.zeros(span, dtype=torch.float32, device="cuda") for _ in range(3)]
-    views = [torch.as_strided(c, (k, L.n_pad), (L.stride, 1)) for c in cand]
+    views = [torch.as_strided(c, (k, L.n_pad), (L.slot, 1)) for c in cand]
     views[0].copy_(ref.theta)
     state = fresh_state(torch, k)
     g = ref.new_grads(torch.float16)
@@ -89,7 +89,7 @@ def test_noalloc_with_binary16_gradients_and_flags():
         assert flags.cpu().tolist() == [0, 0, int(step == 0)]
         ref.inner_step(g, flags=flags)
         D.diloco_inner_step_noalloc(
-            theta=cand[0].data_ptr(), m=cand[1].data_ptr(), v=cand[2].data_ptr(), stride=L.stride,
+            theta=cand[0].data_ptr(), m=cand[1].data_ptr(), v=cand[2].data_ptr(), stride=L.slot,
             n_pad=L.n_pad, k_workers=k, grad_dtype=D.F16, grads=g.data_ptr(), grad_stride=g.stride(0),
             inv_scale=inv, found_inf=flags.data_ptr(), step_state=state.data_ptr(),
             lr=HP["inner_lr"], beta1=HP["beta1"], beta2=HP["beta2"], eps=HP["eps"],
