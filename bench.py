@@ -69,14 +69,15 @@ class Bench:
         self.cursor = self.base
 
     # ------------------------------------------------------------------ set-up
-    def make(self, name, k, H=0, pg=0, round_mean=0, groups=False, g16=False, zeros=False):
+    def make(self, name, k, H=0, pg=0, round_mean=0, groups=False, g16=False, zeros=False,
+             layout_mode=0):
         """A context on the named workload with seeded synthetic weights (matrices ~N(0, 0.02),
         norm vectors 1.0) and one resident seeded gradient set ~N(0, 1e-3) per worker."""
         torch, D, synth = self.torch, self.D, self.synth
         wl = synth.WORKLOADS[name]()
         holder = {}
         self.reset()
-        lay, _ = D.diloco_query_layout(D.make_config(wl.numel, k))
+        lay, _ = D.diloco_query_layout(D.make_config(wl.numel, k, layout_mode=layout_mode))
 
         def fill(theta0, layout, offsets):
             holder["kind"] = self.take(layout.n_pad, torch.uint8)
@@ -86,7 +87,8 @@ class Bench:
                                   stream=self.stream.cuda_stream)
 
         dl = D.DiLoCo(wl.numel, k, fill_theta0=fill, h_inner_steps=H, pg_dtype=pg,
-                      pg_round_mean=round_mean, arena=self.take(lay.arena_bytes, torch.float32))
+                      pg_round_mean=round_mean, layout_mode=layout_mode,
+                      arena=self.take(lay.arena_bytes, torch.float32))
         if self.tune:
             dl.set_tuning(**self.tune)
         if groups:
@@ -181,10 +183,11 @@ class Bench:
         return res
 
     def quick(self, name, k, pg=0, round_mean=0, n_inner=20, n_outer=20, groups=False, tune=None,
-              zeros=False):
+              zeros=False, layout_mode=0):
         """Short timing of both kernels: n_inner inner and n_outer outer launches after two
         warm-up launches of each."""
-        wl, dl, grads = self.make(name, k, pg=pg, round_mean=round_mean, groups=groups, zeros=zeros)
+        wl, dl, grads = self.make(name, k, pg=pg, round_mean=round_mean, groups=groups, zeros=zeros,
+                                  layout_mode=layout_mode)
         if tune:
             dl.set_tuning(**tune)
         n = wl.n_params
@@ -678,6 +681,14 @@ def main():
                         "what the memory system sustains depends on the data" % args.k,
             "zeros": B.quick("llama150m", args.k, zeros=True),
             "synthetic": B.quick("llama150m", args.k)}
+        out["layout_modes"] = {
+            "workload": "k = %d, 20 inner + 20 outer launches per arena order; the automatic choice "
+                        "is buffer-major for the 150M set (0.87 GiB slots) and worker-major for the "
+                        "1.1B set (4.1 GiB slots)" % args.k,
+            **{"%s_%s" % (nm, mode_name): B.quick(nm, args.k, pg=p, layout_mode=mode)
+               for nm, p in (("llama150m", pg), ("llama1.1b", D.F16))
+               for mode, mode_name in ((D.LAYOUT_BUFFER_MAJOR, "buffer_major"),
+                                       (D.LAYOUT_WORKER_MAJOR, "worker_major"))}}
         out["stream_patterns"] = B.stream_patterns()
         out["delayed_outer"] = {"llama150m": B.delayed_outer("llama150m", args.k, pg, 4, 20),
                                 "llama1.1b": B.delayed_outer("llama1.1b", args.k, D.F16, 2, 20)}

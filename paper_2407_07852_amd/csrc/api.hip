@@ -597,6 +597,7 @@ static OuterArgs outer_args(const diloco_ctx* ctx, float* workers) {
   a.k = (int)ctx->cfg.k_workers;
   a.pg = ctx->cfg.pg_dtype;
   a.round_mean = ctx->cfg.pg_round_mean;
+  a.worker_major = ctx->lay.layout_mode == DILOCO_LAYOUT_WORKER_MAJOR;
   return a;
 }
 

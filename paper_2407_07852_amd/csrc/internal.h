@@ -68,6 +68,7 @@ struct OuterArgs {
   int k;
   int pg;          // pseudo-gradient type: 0 binary32, 1 binary16, 2 bfloat16
   int round_mean;  // also round the average through that type
+  int worker_major;  // the arena's order (launch shape only): workers 4 slots apart
 };
 
 // Advances every worker's step state in place (unless its found_inf flag is set) and writes the

@@ -520,7 +520,10 @@ hipError_t launch_inner(const InnerArgs& a, int k, bool g16, bool groups, const 
 // wants one more wave.  One wave off the optimum costs 0.5-5 points.  The run-time-k kernel
 // (k >= 9) has a rule of its own at its launch.
 struct OuterShape { int block, waves; };
-static OuterShape outer_shape(const Tuning& t, int k, int pg) {
+static bool spread_workers(const OuterArgs& a) {
+  return a.worker_major != 0 && a.stride * 4 >= (10ull << 30);
+}
+static OuterShape outer_shape(const Tuning& t, int k, int pg, bool spread) {
   static const int kWaves32[9] = {0, 9, 6, 6, 4, 4, 4, 5, 4};
   static const int kWaves16[9] = {0, 9, 7, 6, 5, 5, 4, 5, 4};
   OuterShape s;
@@ -528,13 +531,16 @@ static OuterShape outer_shape(const Tuning& t, int k, int pg) {
   if (t.outer_waves >= 0) s.waves = t.outer_waves;
   else if (k <= 8) s.waves = pg != 0 ? kWaves16[k] : kWaves32[k];
   else s.waves = 4;
+  // With the workers' weights 10 GiB or more apart (worker-major arena, multi-GiB slots) the
+  // k = 8 step is flat from 5 to 7 waves and 0.3 points better there than at 4 (1.1B set).
+  if (t.outer_waves < 0 && spread && k == 8) s.waves = 5;
   return s;
 }
 
 template <int K, int PG, bool RM, int B>
 static hipError_t launch_outer_t(const OuterArgs& a, const Tuning& t, hipStream_t s) {
   const uint64_t tiles = a.n_pad / (uint64_t)(B * kVecElems);
-  const uint32_t lds = pad_lds_bytes(outer_shape(t, K, PG).waves, B, t.lds_per_cu);
+  const uint32_t lds = pad_lds_bytes(outer_shape(t, K, PG, spread_workers(a)).waves, B, t.lds_per_cu);
   hipLaunchKernelGGL((outer_fused_kernel<K, PG, RM, B>), dim3((uint32_t)tiles), dim3(B), lds, s, a,
                      (uint32_t)tiles);
   return hipGetLastError();
@@ -568,7 +574,7 @@ static hipError_t launch_outer_k(const OuterArgs& a, const Tuning& t, hipStream_
 
 template <int PG, bool RM>
 static hipError_t launch_outer_b(const OuterArgs& a, const Tuning& t, hipStream_t s) {
-  switch (outer_shape(t, a.k, PG).block) {
+  switch (outer_shape(t, a.k, PG, spread_workers(a)).block) {
     case 128: return launch_outer_k<PG, RM, 128>(a, t, s);
     case 256: return launch_outer_k<PG, RM, 256>(a, t, s);
     default: return launch_outer_k<PG, RM, 64>(a, t, s);
