@@ -292,8 +292,8 @@ int diloco_outer_step(diloco_ctx* ctx);
  * With no inner step in between, the pair equals diloco_outer_step bit for bit (finite weights).
  * snapshot: device, caller-owned, k rows of n_pad floats, `slot` floats apart (dense, whatever
  * the arena's layout mode; snapshot_bytes >= ((k-1)*slot + n_pad)*4), 16-byte aligned, untouched
- * by the caller until diloco_outer_finish has run.  side_stream: hipStream_t of the same device (default priority);
- * it may be the context's own stream, in which case nothing overlaps.  Between begin and finish
+ * by the caller until diloco_outer_finish has run.  side_stream: hipStream_t of the same
+ * device (default priority); it may be the context's own stream, in which case nothing overlaps.  Between begin and finish
  * theta0 and mom are in flux: diloco_outer_step and a second diloco_outer_begin return
  * DILOCO_ERR_STATE, and so does diloco_outer_finish without a begin.  begin enqueues two
  * kernels and two event operations, finish one kernel and one; none allocates.
@@ -303,7 +303,9 @@ int diloco_outer_finish(diloco_ctx* ctx);
 
 /* Device address of a flat buffer (replica ignored for THETA0 / MOM): the two model copies and
  * the optimizer states of paragraph "General Implementation Details", e.g. to view a worker's
- * parameter tensors in place at tensor_offsets.  Errors: DILOCO_ERR_INVALID_ARG. */
+ * parameter tensors in place at tensor_offsets; DILOCO_BUF_GRADS is the arena's gradient slot
+ * of that worker, which diloco_init leaves as it finds it (a caller that uses it clears the
+ * pads once).  Errors: DILOCO_ERR_INVALID_ARG. */
 int diloco_get_buffer(diloco_ctx* ctx, int which, uint32_t replica, void** dev_ptr);
 
 /* The layout this context was created with (same values as diloco_query_layout).
