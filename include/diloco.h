@@ -115,10 +115,10 @@ typedef struct {
  * starts r*stride elements after replica 0.
  *   buffer-major: stride = slot; theta0, mom, theta[0..k), m[0..k), v[0..k), grads[0..k).
  *   worker-major: stride = 4*slot; theta0, mom, then theta_r, m_r, v_r, grads_r per worker.
- * The automatic choice is worker-major when 4*slot*4 bytes lies between 10 and 24 GiB (about
- * 0.7 to 1.6 billion parameters per replica), buffer-major otherwise: measured on MI355X, the
- * outer step sustains most when consecutive workers' weights lie 12-20 GiB apart (or directly
- * adjacent, when they are small), and the inner step when a worker's four streams are
+ * The automatic choice is worker-major when a slot holds 2 GiB or more (about 0.54 billion
+ * parameters per replica), buffer-major otherwise: measured on MI355X, the inner step sustains
+ * most when a worker's four streams are adjacent (1.6 to 3 points for such slots), and the outer
+ * step when consecutive workers' weights lie 12-20 GiB apart or, when they are small, directly
  * adjacent.  Results never depend on the mode.
  * The gradient slots are FP32-sized; a caller may write gradients there (FP32: [k] rows of
  * n_pad floats, `stride` floats apart; binary16: rows of n_pad halves, 2*stride halves apart)

@@ -132,18 +132,16 @@ void plan(const diloco_config* cfg, diloco_layout* lay, uint64_t* offsets) {
   // larger alignments and skews between the buffers measured neutral or worse).
   const uint64_t slot = round_up(n_pad, DILOCO_STRIDE_ALIGN_BYTES / 4);
   const uint64_t sb = slot * 4;  // bytes per slot
-  // Which order: measured on MI355X at k = 8, the outer step sustains most when consecutive
-  // workers' weights lie 12-20 GiB apart (80.5-80.9 % of peak against 79.2 % for adjacent 4 GiB
-  // buffers) and the inner step when a worker's four streams are adjacent (82.1 % against
-  // 81.2 %); with small buffers (0.9 GiB) adjacent worker weights are best for the outer step
-  // (80.2 % against 79.1 % with 3.5 GiB between them).  Worker-major spaces the workers 4 slots
-  // apart, so it is chosen when that distance falls in the good range.
+  // Which order: measured on MI355X, the inner step sustains most when a worker's four streams
+  // are adjacent -- by 1.6 to 3 points for slots of 2 GiB and more (0.6 to 3.5 B parameters,
+  // k = 4 and 8), within +-0.5 point for smaller slots -- and the outer step when consecutive
+  // workers' weights lie 12-20 GiB apart or, for small slots, directly adjacent (150M set, k = 8:
+  // 80.2 % adjacent against 79.1 % with 3.5 GiB between them; 1.1B set: 80.9 % at 16.4 GiB against
+  // 79.2 % adjacent).  Worker-major spaces the workers 4 slots apart.  The inner step runs H
+  // times per outer step, so it decides from 2 GiB slots on; below that the outer step does.
   int mode = cfg->layout_mode;
-  if (mode == DILOCO_LAYOUT_AUTO) {
-    const uint64_t gib = 1ull << 30, spacing = 4 * sb;
-    mode = (spacing >= 10 * gib && spacing <= 24 * gib) ? DILOCO_LAYOUT_WORKER_MAJOR
-                                                        : DILOCO_LAYOUT_BUFFER_MAJOR;
-  }
+  if (mode == DILOCO_LAYOUT_AUTO)
+    mode = sb >= (2ull << 30) ? DILOCO_LAYOUT_WORKER_MAJOR : DILOCO_LAYOUT_BUFFER_MAJOR;
   lay->slot = slot;
   lay->layout_mode = mode;
   lay->reserved = 0;

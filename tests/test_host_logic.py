@@ -76,14 +76,13 @@ def test_layout_agrees_with_oracle_planner():
 
 
 def test_automatic_layout_choice_by_buffer_size():
-    """Worker-major exactly when four slots span 10 to 24 GiB (the 1.1B set: 4.1 GiB slots)."""
+    """Worker-major exactly when a slot holds 2 GiB or more (the 1.1B set: 4.1 GiB slots)."""
     D = _D()
-    gib = 1 << 30
+    two_gib = (2 << 30) // 4   # elements
     for n, want in ((787456, D.LAYOUT_BUFFER_MAJOR), (234119168, D.LAYOUT_BUFFER_MAJOR),
-                    (10 * gib // 16 - 524288, D.LAYOUT_BUFFER_MAJOR),
-                    (10 * gib // 16, D.LAYOUT_WORKER_MAJOR),
-                    (1100046336, D.LAYOUT_WORKER_MAJOR), (24 * gib // 16, D.LAYOUT_WORKER_MAJOR),
-                    (24 * gib // 16 + 1, D.LAYOUT_BUFFER_MAJOR), (1 << 32, D.LAYOUT_BUFFER_MAJOR)):
+                    (two_gib - 524288, D.LAYOUT_BUFFER_MAJOR), (two_gib - 524287, D.LAYOUT_WORKER_MAJOR),
+                    (two_gib, D.LAYOUT_WORKER_MAJOR), (1100046336, D.LAYOUT_WORKER_MAJOR),
+                    (1 << 32, D.LAYOUT_WORKER_MAJOR)):
         lay, _ = D.diloco_query_layout(D.make_config([n], 4))
         assert lay.layout_mode == want, (n, lay.layout_mode)
     with pytest.raises(D.DilocoError):
