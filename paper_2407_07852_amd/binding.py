@@ -290,6 +290,18 @@ class DiLoCo:
         flat = out[:self.grads_numel()].zero_()
         return torch.as_strided(flat, (self.k, L.n_pad), (L.slot, 1))
 
+    def tensors(self, row, shapes):
+        """Per-tensor views of one flat row (a worker's weights `theta[r]`, its gradients
+        `new_grads()[r]`, `theta0`, a moment row): the parameter tensor list of the model, in
+        place.  shapes: one shape per tensor of the list given at construction."""
+        assert len(shapes) == len(self.numel)
+        out = []
+        for off, n, shape in zip(self.offsets, self.numel, shapes):
+            view = row[off:off + n].view(*shape)
+            assert view.numel() == n, "shape %r does not hold %d elements" % (tuple(shape), n)
+            out.append(view)
+        return out
+
     def new_flags(self):
         return torch.zeros(self.k, dtype=torch.int32, device=self.device)
 

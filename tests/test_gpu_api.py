@@ -195,6 +195,38 @@ def test_layout_modes_give_identical_results_and_accessors_agree():
         side.dl.close()
 
 
+def test_per_tensor_views_alias_the_flat_buffers():
+    """A model's parameters and gradients as views of the arena: writing through the views is
+    what the steps see, and what the steps write is what the views show."""
+    import torch
+    import paper_2407_07852_amd as D
+    shapes = [(3, 50), (7,), (64, 2), (1,)]
+    numel = [150, 7, 128, 1]
+    k = 2
+    init = [torch.full(sh, float(j + 1), device="cuda") for j, sh in enumerate(shapes)]
+    dl = D.DiLoCo(numel, k, init_params=init, inner_lr=0.5, weight_decay=0.0)
+    grads = dl.new_grads()
+    for r in range(k):
+        params = dl.tensors(dl.theta[r], shapes)
+        gviews = dl.tensors(grads[r], shapes)
+        for j, (p, g) in enumerate(zip(params, gviews)):
+            assert p.shape == torch.Size(shapes[j]) and torch.all(p == j + 1)
+            g.fill_(1.0 if r == 0 else -1.0)
+    dl.inner_step(grads)
+    torch.cuda.synchronize()
+    # first AdamW step with |g| = 1: every element moves by lr against the gradient's sign
+    for r, sign in ((0, -1.0), (1, 1.0)):
+        for j, p in enumerate(dl.tensors(dl.theta[r], shapes)):
+            assert torch.allclose(p, torch.full_like(p, j + 1 + sign * 0.5), atol=1e-6)
+    # the pads between the tensors stayed zero
+    flat = dl.theta[0]
+    used = torch.zeros(dl.layout.n_pad, dtype=torch.bool, device="cuda")
+    for off, n in zip(dl.offsets, numel):
+        used[off:off + n] = True
+    assert not flat[~used].any()
+    dl.close()
+
+
 def test_error_paths():
     import torch
     import paper_2407_07852_amd as D
