@@ -15,11 +15,12 @@ def _ragged(n):
                                            for j, s in enumerate(synth.ragged_sizes(n))])
 
 
-@pytest.mark.parametrize("k", [1, 3, 5, 8, 9, 16, 33, 64])
+@pytest.mark.parametrize("k,layout_mode", [(1, 0), (3, 0), (5, 0), (8, 0), (9, 0), (16, 0), (33, 0),
+                                           (64, 0), (1, 2), (8, 2), (9, 2), (64, 2)])
 @pytest.mark.parametrize("pg_f16", [False, True])
-def test_round_for_various_k(k, pg_f16):
+def test_round_for_various_k(k, layout_mode, pg_f16):
     wl = _ragged(40)
-    gpu, cpu = GpuSide(wl, k, pg_f16, h=3), CpuSide(wl, k, pg_f16)
+    gpu, cpu = GpuSide(wl, k, pg_f16, h=3, layout_mode=layout_mode), CpuSide(wl, k, pg_f16)
     for step in range(3):
         gpu.dl.inner_step(gpu.gen_grads(step))
         cpu.o.inner_step(cpu.gen_grads(step))
