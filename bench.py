@@ -163,8 +163,18 @@ class Bench:
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
         in_round_ms = list(outer_ms)
+        batch_ms = None
         if extra_outer:
             outer_ms += self.time_launches(dl.outer_step, extra_outer)
+            # the same number of launches once more between ONE pair of events: what a launch
+            # takes when no event record sits between consecutive launches
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(self.stream)
+            for _ in range(extra_outer):
+                dl.outer_step()
+            e1.record(self.stream)
+            e1.synchronize()
+            batch_ms = e0.elapsed_time(e1) / extra_outer
         done = (H if warmup_inner is None else warmup_inner) * warmup_rounds + H * rounds
         assert dl.steps() == [done] * k
         finite = bool(torch.isfinite(dl.theta0).all())
@@ -178,6 +188,11 @@ class Bench:
                "round_ms": round_ms, "round_GBps": (H * ib + ob) / round_ms / 1e6,
                "outer": stats(outer_ms, ob),
                "outer_in_rounds": stats(in_round_ms, ob)}
+        if batch_ms is not None:
+            res["outer"]["ms_back_to_back"] = batch_ms
+            res["outer"]["frac_of_peak_back_to_back"] = ob / batch_ms / 1e6 / HBM_PEAK_GBS
+            res["outer"]["note"] = ("ms / frac_of_peak: every launch between its own pair of events; "
+                                    "back_to_back: %d launches between one pair" % extra_outer)
         if H:
             res["inner"] = stats(inner_ms, ib)
         return res
