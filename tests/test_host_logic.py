@@ -37,8 +37,27 @@ def test_header_constants_match_binding():
                       ("DILOCO_TILE", D.TILE)):
         assert int(re.search(name + r"\s+(\d+)", header).group(1)) == val
     for name in ("OK", "ROUND_COMPLETE", "ERR_INVALID_ARG", "ERR_ALIGN", "ERR_ARENA_TOO_SMALL",
-                 "ERR_HIP", "ERR_STATE"):
+                 "ERR_HIP", "ERR_STATE", "F32", "F16", "BF16", "BUF_THETA0", "BUF_MOM", "BUF_THETA",
+                 "BUF_M", "BUF_V", "BUF_GRADS", "LAYOUT_AUTO", "LAYOUT_BUFFER_MAJOR",
+                 "LAYOUT_WORKER_MAJOR"):
         assert int(re.search(r"DILOCO_" + name + r"\s*=\s*(-?\d+)", header).group(1)) == getattr(D, name)
+
+
+def test_binding_structs_have_the_headers_sizes(tmp_path):
+    """The ctypes mirrors of the header's structs against a C probe compiled from the header."""
+    import subprocess
+    D = _D()
+    src = tmp_path / "probe.c"
+    src.write_text('#include <stdio.h>\n#include "%s"\nint main(void) { printf("%%zu %%zu %%zu %%zu\\n", '
+                   'sizeof(diloco_config), sizeof(diloco_layout), sizeof(diloco_inner_call), '
+                   'sizeof(diloco_step_state)); return 0; }\n'
+                   % os.path.join(ROOT, "include", "diloco.h"))
+    exe = tmp_path / "probe"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", str(src), "-o", str(exe)], check=True)
+    sizes = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True,
+                                            text=True).stdout.split()]
+    assert sizes == [ctypes.sizeof(D.Config), ctypes.sizeof(D.Layout), ctypes.sizeof(D.InnerCall),
+                     D.STEP_STATE_BYTES]
 
 
 def test_layout_agrees_with_oracle_planner():
