@@ -116,7 +116,7 @@ typedef struct {
  *   buffer-major: stride = slot; theta0, mom, theta[0..k), m[0..k), v[0..k), grads[0..k).
  *   worker-major: stride = 4*slot; theta0, mom, then theta_r, m_r, v_r, grads_r per worker.
  * The automatic choice is worker-major when a slot holds 2 GiB or more (about 0.54 billion
- * parameters per replica), buffer-major otherwise: measured on MI355X, the inner step sustains
+ * parameters per replica) or the whole arena exceeds 64 GiB, buffer-major otherwise: measured on MI355X, the inner step sustains
  * most when a worker's four streams are adjacent (1.6 to 3 points for such slots), and the outer
  * step when consecutive workers' weights lie 12-20 GiB apart or, when they are small, directly
  * adjacent.  Results never depend on the mode.

@@ -138,10 +138,14 @@ void plan(const diloco_config* cfg, diloco_layout* lay, uint64_t* offsets) {
   // workers' weights lie 12-20 GiB apart or, for small slots, directly adjacent (150M set, k = 8:
   // 80.2 % adjacent against 79.1 % with 3.5 GiB between them; 1.1B set: 80.9 % at 16.4 GiB against
   // 79.2 % adjacent).  Worker-major spaces the workers 4 slots apart.  The inner step runs H
-  // times per outer step, so it decides from 2 GiB slots on; below that the outer step does.
+  // times per outer step, so it decides from 2 GiB slots on; below that the outer step does --
+  // unless the arena outgrows 64 GiB, the period of the memory system's position effect: then
+  // buffer-major puts a worker's four streams into different 64 GiB blocks and loses on both
+  // steps whatever the slot size (150M set, k = 24: inner 79.0 / outer 74.6 % against 83.1 / 77.9 %).
   int mode = cfg->layout_mode;
   if (mode == DILOCO_LAYOUT_AUTO)
-    mode = sb >= (2ull << 30) ? DILOCO_LAYOUT_WORKER_MAJOR : DILOCO_LAYOUT_BUFFER_MAJOR;
+    mode = (sb >= (2ull << 30) || (2 + 4 * k) * sb > (64ull << 30)) ? DILOCO_LAYOUT_WORKER_MAJOR
+                                                                   : DILOCO_LAYOUT_BUFFER_MAJOR;
   lay->slot = slot;
   lay->layout_mode = mode;
   lay->reserved = 0;

@@ -95,7 +95,8 @@ def test_layout_agrees_with_oracle_planner():
 
 
 def test_automatic_layout_choice_by_buffer_size():
-    """Worker-major exactly when a slot holds 2 GiB or more (the 1.1B set: 4.1 GiB slots)."""
+    """Worker-major exactly when a slot holds 2 GiB or more (the 1.1B set: 4.1 GiB slots) or the
+    arena exceeds 64 GiB."""
     D = _D()
     two_gib = (2 << 30) // 4   # elements
     for n, want in ((787456, D.LAYOUT_BUFFER_MAJOR), (234119168, D.LAYOUT_BUFFER_MAJOR),
@@ -104,6 +105,11 @@ def test_automatic_layout_choice_by_buffer_size():
                     (1 << 32, D.LAYOUT_WORKER_MAJOR)):
         lay, _ = D.diloco_query_layout(D.make_config([n], 4))
         assert lay.layout_mode == want, (n, lay.layout_mode)
+    # the 150M set (0.87 GiB slots): 34 slots at k = 8 and 70 at k = 17 fit 64 GiB, 74 at k = 18 do not
+    for k, want in ((8, D.LAYOUT_BUFFER_MAJOR), (17, D.LAYOUT_BUFFER_MAJOR), (18, D.LAYOUT_WORKER_MAJOR),
+                    (64, D.LAYOUT_WORKER_MAJOR)):
+        lay, _ = D.diloco_query_layout(D.make_config([234119168], k))
+        assert lay.layout_mode == want and (lay.arena_bytes > (64 << 30)) == (want == D.LAYOUT_WORKER_MAJOR)
     with pytest.raises(D.DilocoError):
         D.diloco_query_layout(D.make_config([4], 2, layout_mode=3))
 
